@@ -1,0 +1,193 @@
+"""CPU oracle for the prefill KV-eviction path of CodeComp: score -> select -> gather.
+
+TEST INFRASTRUCTURE ONLY.  This is the plain fp64 definition of what the HIP path must
+compute, written straight from the paper's equations, with no blocking, fusion or
+reordering.  It shares no code with the HIP path and must never be imported by it; only
+tests, the smoke check and the benchmark's CPU-baseline leg may call it.
+
+What it follows (paper sections / equations):
+
+  * Section "Attention-based KV Cache Compression", its only equation
+        A = softmax(Q K^T / sqrt(d)),   u(j) = sum_{t=1..W} A(t, j)
+    with Q the W observation-window queries and K the cached keys; the softmax of one
+    query row runs over every cached key (the equation carries no mask).
+  * Appendix "Compression settings": the attention scores are average-pooled over a
+    sliding window (size 5 in the paper; the width is a parameter here).
+  * Sections "Span-Level Structural Protection" / "Attention-based KV Cache Compression":
+    structure decides what must be kept and attention fills the remaining capacity.  The
+    paper states this as a two-stage rule and gives no formula that mixes a dense per-token
+    prior with the attention mass.  The reading used throughout this repository is
+        c(j) = pooled_u(j) + lambda * p(j)
+    followed by ONE top-(B - W) over the prefix [0, N - W); its lambda -> infinity limit
+    with a binary prior is the paper's "protected tokens first, attention fills the rest".
+    PARITY UNPINNED BY THE PAPER for this combination rule: no worked example or printed
+    number distinguishes the additive reading from the two-stage rule.  It is pinned only
+    by closed forms (lambda = 0, lambda large) and brute force.
+  * "We retain the top-ranked context tokens ... up to the remaining chunk budget" and
+    "Compression is applied independently at each transformer layer": selection is per
+    layer (and here per KV head), and the compact cache holds the retained K/V rows in
+    their original order.
+
+Readings where the paper is silent (all listed again in the design notes of this repo):
+  - grouped-query attention: the G query heads sharing one KV head are averaged (mean);
+  - pooling: stride 1, same length, zero padding, divisor always k, over the whole row;
+  - the last W tokens (the observation window itself) are always kept and count towards B;
+  - ties between equal scores go to the lower token index;
+  - kept indices are emitted in ascending order.
+
+All arrays are numpy.  bf16 inputs arrive as uint16 bit patterns and are widened exactly.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of bfloat16 bit patterns (uint16) to float64."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return b.view(np.float32).astype(np.float64)
+
+
+# ----------------------------------------------------------------------------------------
+# score
+# ----------------------------------------------------------------------------------------
+
+def attention_rows(q: np.ndarray, k: np.ndarray, scale: float) -> np.ndarray:
+    """A = softmax(q k^T * scale) for one query head: q [W, d], k [N, d] -> A [W, N].
+    (The equation of section "Attention-based KV Cache Compression"; rows sum to 1.)"""
+    s = (q @ k.T) * scale
+    s = s - s.max(axis=1, keepdims=True)          # stabiliser: leaves the softmax unchanged
+    e = np.exp(s)
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def window_attention_mass(q_obs: np.ndarray, k: np.ndarray, scale: float | None = None) -> np.ndarray:
+    """u[h, j] = (1/G) sum_{g<G} sum_{t<W} A[h*G+g][t, j].
+
+    q_obs float64 [H_q, W, d]; k float64 [H_kv, N, d]; returns float64 [H_kv, N].
+    Query head h_q reads KV head h_q // G (contiguous grouping)."""
+    h_q, w, d = q_obs.shape
+    h_kv, n, d2 = k.shape
+    assert d == d2 and h_q % h_kv == 0
+    g = h_q // h_kv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    u = np.zeros((h_kv, n), dtype=np.float64)
+    for hq in range(h_q):
+        a = attention_rows(q_obs[hq], k[hq // g], scale)
+        u[hq // g] += a.sum(axis=0)               # u(j) = sum_t A(t, j)
+    return u / g
+
+
+def average_pool(u: np.ndarray, kernel: int) -> np.ndarray:
+    """pooled[j] = (1/k) sum_{|delta| <= (k-1)/2} u[j + delta], terms outside [0, N) are zero.
+    Works on the last axis."""
+    assert kernel >= 1 and kernel % 2 == 1
+    half = (kernel - 1) // 2
+    n = u.shape[-1]
+    out = np.zeros_like(u, dtype=np.float64)
+    for delta in range(-half, half + 1):
+        lo, hi = max(0, -delta), min(n, n - delta)        # j with 0 <= j + delta < n
+        if hi > lo:
+            out[..., lo:hi] += u[..., lo + delta:hi + delta]
+    return out / kernel
+
+
+def fuse_prior(pooled: np.ndarray, prior: np.ndarray, prior_weight: float) -> np.ndarray:
+    """c[h, j] = pooled[h, j] + lambda * p[j]; the prior is shared by all heads."""
+    return pooled + float(prior_weight) * np.asarray(prior, dtype=np.float64)[None, :]
+
+
+def score(q_obs: np.ndarray, k: np.ndarray, prior: np.ndarray, *, pool_kernel: int,
+          prior_weight: float, scale: float | None = None) -> np.ndarray:
+    """Scores of one request in one layer: float64 [H_kv, N]."""
+    u = window_attention_mass(q_obs, k, scale)
+    return fuse_prior(average_pool(u, pool_kernel), prior, prior_weight)
+
+
+# ----------------------------------------------------------------------------------------
+# select
+# ----------------------------------------------------------------------------------------
+
+def select(scores: np.ndarray, window: int, budget: int) -> np.ndarray:
+    """Kept token indices per head: int64 [H, budget], ascending.
+
+    The last `window` tokens are always kept.  The other budget - window come from the
+    prefix [0, N - window): rank it by (score descending, index ascending) and take the
+    head of that ranking."""
+    h, n = scores.shape
+    assert 1 <= window <= n and window <= budget <= n
+    take = budget - window
+    out = np.empty((h, budget), dtype=np.int64)
+    tail = np.arange(n - window, n, dtype=np.int64)
+    for i in range(h):
+        prefix = scores[i, : n - window]
+        order = np.argsort(-prefix, kind="stable")        # stable: equal scores keep index order
+        out[i] = np.concatenate([np.sort(order[:take]), tail])
+    return out
+
+
+# ----------------------------------------------------------------------------------------
+# gather
+# ----------------------------------------------------------------------------------------
+
+def gather(k: np.ndarray, v: np.ndarray, idx: np.ndarray):
+    """k_out[h, i, :] = k[h, idx[h, i], :], same for v (a copy of rows; any dtype)."""
+    h = k.shape[0]
+    k_out = np.stack([k[i][idx[i]] for i in range(h)])
+    v_out = np.stack([v[i][idx[i]] for i in range(h)])
+    return k_out, v_out
+
+
+# ----------------------------------------------------------------------------------------
+# whole path: layers x requests (packed / ragged)
+# ----------------------------------------------------------------------------------------
+
+def score_packed(q_bits, k_bits, prior, cu_seqlens, *, pool_kernel, prior_weight, scale=None,
+                 layers=None) -> np.ndarray:
+    """q_bits uint16 [L][n_seqs][H_q][W][d], k_bits uint16 [L][H_kv][T][d], prior [T],
+    cu_seqlens [n_seqs+1] -> scores float64 [L][H_kv][T].  Every (layer, request) is scored
+    on its own; layers not listed in `layers` are left as NaN."""
+    n_layers, h_kv, total, _ = k_bits.shape
+    out = np.full((n_layers, h_kv, total), np.nan, dtype=np.float64)
+    for l in (range(n_layers) if layers is None else layers):
+        for r in range(len(cu_seqlens) - 1):
+            a, b = int(cu_seqlens[r]), int(cu_seqlens[r + 1])
+            out[l, :, a:b] = score(bf16_bits_to_f64(q_bits[l, r]), bf16_bits_to_f64(k_bits[l, :, a:b]),
+                                   prior[a:b], pool_kernel=pool_kernel, prior_weight=prior_weight, scale=scale)
+    return out
+
+
+def select_packed(scores, cu_seqlens, cu_budgets, window) -> np.ndarray:
+    """scores [L][H][T] -> idx int64 [L][H][sum B_r]; indices are local to their request."""
+    n_layers, h, _ = scores.shape
+    out = np.empty((n_layers, h, int(cu_budgets[-1])), dtype=np.int64)
+    for l in range(n_layers):
+        for r in range(len(cu_seqlens) - 1):
+            a, b = int(cu_seqlens[r]), int(cu_seqlens[r + 1])
+            oa, ob = int(cu_budgets[r]), int(cu_budgets[r + 1])
+            out[l, :, oa:ob] = select(scores[l, :, a:b], window, ob - oa)
+    return out
+
+
+def gather_packed(k, v, idx, cu_seqlens, cu_budgets):
+    """k, v [L][H][T][d] (any dtype), idx [L][H][sum B_r] request-local -> compact [L][H][sum B_r][d]."""
+    n_layers, h, _, d = k.shape
+    k_out = np.empty((n_layers, h, int(cu_budgets[-1]), d), dtype=k.dtype)
+    v_out = np.empty_like(k_out, dtype=v.dtype)
+    for l in range(n_layers):
+        for r in range(len(cu_seqlens) - 1):
+            a, b = int(cu_seqlens[r]), int(cu_seqlens[r + 1])
+            oa, ob = int(cu_budgets[r]), int(cu_budgets[r + 1])
+            k_out[l, :, oa:ob], v_out[l, :, oa:ob] = gather(k[l, :, a:b], v[l, :, a:b], idx[l, :, oa:ob])
+    return k_out, v_out
+
+
+def compress_packed(q_bits, k_bits, v_bits, prior, cu_seqlens, cu_budgets, *, window, pool_kernel,
+                    prior_weight, scale=None):
+    """The whole path.  Returns (scores, idx, k_out, v_out)."""
+    sc = score_packed(q_bits, k_bits, prior, cu_seqlens, pool_kernel=pool_kernel,
+                      prior_weight=prior_weight, scale=scale)
+    idx = select_packed(sc, cu_seqlens, cu_budgets, window)
+    k_out, v_out = gather_packed(k_bits, v_bits, idx, cu_seqlens, cu_budgets)
+    return sc, idx, k_out, v_out
