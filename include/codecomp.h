@@ -1,0 +1,126 @@
+/*
+ * codecomp.h - C ABI of the MI355X (gfx950) prefill KV-eviction path of CodeComp:
+ *              score -> select -> gather.
+ *
+ * The operation is the one stated in the paper's section "Attention-based KV Cache
+ * Compression": with Q the W observation-window queries and K the N cached keys of one
+ * attention head,  A = softmax(Q K^T / sqrt(d)),  u(j) = sum_t A(t, j);  the scores are
+ * average-pooled over a sliding window (appendix "Compression settings"), combined with the
+ * structural prior of section "Span-Level Structural Protection", the top-ranked tokens are
+ * retained up to the budget, independently at each transformer layer, and the retained K/V
+ * rows form the compact cache.
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers unless the name ends in _host.  bf16 tensors are
+ *     passed as `const void*` (16-bit patterns).  The library allocates nothing, keeps no
+ *     state and never synchronises: work is enqueued on `hip_stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream) and the call returns.
+ *   - Query head h_q reads KV head h_q / G with G = n_q_heads / n_kv_heads; the G heads of a
+ *     group are averaged.
+ *   - Requests are packed along the token axis: request r owns tokens
+ *     [cu_seqlens[r], cu_seqlens[r+1]) and output slots [cu_budgets[r], cu_budgets[r+1]).
+ *     Its length is N_r and its budget B_r (the last W tokens are always kept and count
+ *     towards B_r, so W <= B_r <= N_r).  T = cu_seqlens[n_seqs], TB = cu_budgets[n_seqs].
+ *   - Layouts (innermost dimension contiguous; a stride of 0 selects the dense default):
+ *       q_obs  bf16 [n_layers][n_seqs][n_q_heads][W][d]
+ *       k, v   bf16 [n_layers][n_kv_heads][T][d]
+ *       prior  f32  [T]                      (one value per token, shared by layers and heads,
+ *                                             finite and >= 0)
+ *       scores f32  [n_layers][n_kv_heads][T]          (dense)
+ *       idx    i32  [n_layers][n_kv_heads][TB]         (dense; request-local token indices,
+ *                                                       ascending within a request)
+ *       k_out, v_out bf16 [n_layers][n_kv_heads][TB][d]
+ *   - Return value: 0 on success; a negative CODECOMP_E* code when an argument is rejected
+ *     (checked on the host before anything is launched: nothing has been enqueued); a positive
+ *     value is a hipError_t reported by a launch.  Device data is not validated.
+ *   - Inputs are read-only; outputs and workspace must not alias inputs or each other.
+ *     Results are deterministic: the same inputs give bit-identical outputs on every call.
+ */
+#ifndef CODECOMP_H
+#define CODECOMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  CODECOMP_OK = 0,
+  CODECOMP_EINVAL_NULL = -1,      /* a required pointer is NULL                                  */
+  CODECOMP_EINVAL_SHAPE = -2,     /* n_layers < 1, n_seqs < 1, a negative stride, G*W too large   */
+  CODECOMP_EINVAL_WINDOW = -3,    /* W < 1 or W > N_r for some request                            */
+  CODECOMP_EINVAL_BUDGET = -4,    /* B_r < W or B_r > N_r for some request                        */
+  CODECOMP_EINVAL_POOL = -5,      /* pool_kernel even or < 1                                      */
+  CODECOMP_EINVAL_HEADS = -6,     /* n_kv_heads < 1 or n_q_heads not a multiple of n_kv_heads     */
+  CODECOMP_EINVAL_HEADDIM = -7,   /* head_dim not in {64, 128}                                    */
+  CODECOMP_EINVAL_SEQLENS = -8,   /* cu_seqlens / cu_budgets not starting at 0 or not increasing  */
+  CODECOMP_EINVAL_WORKSPACE = -9, /* workspace NULL, misaligned (256 B) or too small              */
+  CODECOMP_EINVAL_PRIOR = -10     /* prior_weight negative or not finite; softmax_scale < 0       */
+};
+
+typedef struct codecomp_params {
+  int32_t n_layers;            /* layers are independent problems batched in one call; >= 1      */
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;            /* d: 64 or 128                                                    */
+  int32_t window;              /* W: the last W tokens of a request are the observation queries   */
+  int32_t pool_kernel;         /* k: odd, >= 1 (1 = no pooling)                                   */
+  float prior_weight;          /* lambda >= 0                                                     */
+  float softmax_scale;         /* 0 selects 1/sqrt(head_dim)                                      */
+  int32_t n_seqs;              /* number of packed requests; 1 = dense                            */
+  int32_t reserved0;           /* must be 0                                                       */
+  const int32_t* cu_seqlens_host; /* [n_seqs+1] HOST copy: sizes the launches and is validated    */
+  const int32_t* cu_seqlens_dev;  /* [n_seqs+1] DEVICE copy of the same values                    */
+  const int32_t* cu_budgets_host; /* [n_seqs+1] HOST                                              */
+  const int32_t* cu_budgets_dev;  /* [n_seqs+1] DEVICE                                            */
+  /* strides in elements; 0 = dense default for the layouts above */
+  int64_t q_stride_layer, q_stride_seq, q_stride_head, q_stride_tok;
+  int64_t kv_stride_layer, kv_stride_head, kv_stride_tok;      /* shared by k and v              */
+  int64_t out_stride_layer, out_stride_head, out_stride_tok;   /* shared by k_out and v_out      */
+} codecomp_params;
+
+/* Host-only: bytes of device workspace the calls below need for these parameters (the largest
+ * of score / select / compress).  Returns 0 when the parameters are invalid. Never touches a GPU. */
+size_t codecomp_workspace_bytes(const codecomp_params* params);
+
+/* Host-only: validates parameters exactly as the launching calls do (0 or a CODECOMP_E* code). */
+int codecomp_validate(const codecomp_params* params);
+
+/* scores[l][h][j] = pooled_u[l][h][j] + lambda * prior[j], where u is the window attention mass
+ * of the equation above averaged over the query-head group, and pooled_u its zero-padded
+ * stride-1 average over pool_kernel neighbours (divisor always pool_kernel), per request.
+ * Logits and probabilities are computed in fp32 from the bf16 inputs (bf16 MFMA products are
+ * exact, accumulation fp32).  workspace: >= codecomp_workspace_bytes(), 256-byte aligned. */
+int codecomp_score(const void* q_obs, const void* k, const float* prior, const codecomp_params* params,
+                   float* scores, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Per (layer, KV head, request): keep tokens N_r-W .. N_r-1, add the B_r - W tokens of the
+ * prefix [0, N_r - W) with the largest scores (equal scores: the lower index wins; scores are
+ * ordered as IEEE floats, -0 == +0, NaN unspecified), write the B_r indices in ascending
+ * order.  Follows "retain the top-ranked context tokens ... up to the remaining chunk budget". */
+int codecomp_select(const float* scores, const codecomp_params* params, int32_t* idx,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* k_out[l][h][cu_budgets[r] + i][:] = k[l][h][cu_seqlens[r] + idx[l][h][cu_budgets[r] + i]][:],
+ * same for v: a bit copy of the retained rows (the compact per-layer cache).  idx values must lie
+ * in [0, N_r). */
+int codecomp_gather(const void* k, const void* v, const int32_t* idx, const codecomp_params* params,
+                    void* k_out, void* v_out, void* hip_stream);
+
+/* The three steps above enqueued back to back in one call; `scores` and `idx` are outputs too. */
+int codecomp_compress(const void* q_obs, const void* k, const void* v, const float* prior,
+                      const codecomp_params* params, float* scores, int32_t* idx, void* k_out, void* v_out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Host-only: static description of a status code returned by the calls above. */
+const char* codecomp_status_string(int status);
+
+/* Host-only: library version as major*10000 + minor*100 + patch. */
+int codecomp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CODECOMP_H */

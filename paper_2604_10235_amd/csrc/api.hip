@@ -1,0 +1,192 @@
+// C ABI of libcodecomp: argument validation, workspace layout and the enqueue order of the
+// score -> select -> gather path.  Everything here runs on the host; validation happens before
+// the first HIP call so that rejected arguments never reach a GPU.
+#include <math.h>
+#include <stdlib.h>
+
+#include "plan.h"
+
+namespace codecomp {
+
+static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+static int chunk_keys_setting() {
+  // Keys per workgroup of the score passes.  CODECOMP_CHUNK_KEYS overrides the default for
+  // experiments (multiple of the LDS tile, at least one tile).
+  static int cached = 0;
+  if (cached == 0) {
+    int v = 1024;
+    if (const char* e = getenv("CODECOMP_CHUNK_KEYS")) {
+      int x = atoi(e);
+      if (x >= kTileKeys && x % kTileKeys == 0 && x <= (1 << 20)) v = x;
+    }
+    cached = v;
+  }
+  return cached;
+}
+
+int make_plan(const codecomp_params* p, Plan* pl) {
+  if (!p) return CODECOMP_EINVAL_NULL;
+  if (p->n_layers < 1 || p->n_seqs < 1 || p->n_seqs > 65535 || p->reserved0 != 0) return CODECOMP_EINVAL_SHAPE;
+  if ((int64_t)p->n_layers * p->n_kv_heads > 65535) return CODECOMP_EINVAL_SHAPE;   // one grid axis
+  if (p->n_kv_heads < 1 || p->n_q_heads < 1 || p->n_q_heads % p->n_kv_heads != 0) return CODECOMP_EINVAL_HEADS;
+  if (p->head_dim != 64 && p->head_dim != 128) return CODECOMP_EINVAL_HEADDIM;
+  if (p->pool_kernel < 1 || p->pool_kernel % 2 == 0) return CODECOMP_EINVAL_POOL;
+  if (!(p->prior_weight >= 0.0f) || !isfinite(p->prior_weight)) return CODECOMP_EINVAL_PRIOR;
+  if (!(p->softmax_scale >= 0.0f) || !isfinite(p->softmax_scale)) return CODECOMP_EINVAL_PRIOR;
+  if (!p->cu_seqlens_host || !p->cu_seqlens_dev || !p->cu_budgets_host || !p->cu_budgets_dev)
+    return CODECOMP_EINVAL_NULL;
+  if (p->window < 1) return CODECOMP_EINVAL_WINDOW;
+  if (p->cu_seqlens_host[0] != 0 || p->cu_budgets_host[0] != 0) return CODECOMP_EINVAL_SEQLENS;
+  int max_n = 0;
+  for (int r = 0; r < p->n_seqs; ++r) {
+    int64_t n = (int64_t)p->cu_seqlens_host[r + 1] - p->cu_seqlens_host[r];
+    int64_t b = (int64_t)p->cu_budgets_host[r + 1] - p->cu_budgets_host[r];
+    if (n < 1 || b < 0) return CODECOMP_EINVAL_SEQLENS;
+    if (p->window > n) return CODECOMP_EINVAL_WINDOW;
+    if (b < p->window || b > n) return CODECOMP_EINVAL_BUDGET;
+    if (n > max_n) max_n = (int)n;
+  }
+  const int64_t strides[] = {p->q_stride_layer, p->q_stride_seq, p->q_stride_head, p->q_stride_tok,
+                             p->kv_stride_layer, p->kv_stride_head, p->kv_stride_tok,
+                             p->out_stride_layer, p->out_stride_head, p->out_stride_tok};
+  for (int64_t s : strides)
+    if (s < 0 || s % 8 != 0) return CODECOMP_EINVAL_SHAPE;   // rows are moved as 16-byte pieces
+
+  pl->L = p->n_layers; pl->Hq = p->n_q_heads; pl->Hkv = p->n_kv_heads; pl->G = pl->Hq / pl->Hkv;
+  pl->d = p->head_dim; pl->W = p->window; pl->pool = p->pool_kernel; pl->n_seqs = p->n_seqs;
+  pl->lambda = p->prior_weight;
+  pl->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
+  pl->T = p->cu_seqlens_host[p->n_seqs];
+  pl->TB = p->cu_budgets_host[p->n_seqs];
+  pl->max_n = max_n;
+  int64_t R = (int64_t)pl->G * pl->W;
+  if (R > (1 << 16)) return CODECOMP_EINVAL_SHAPE;
+  pl->R = (int)R;
+  const int max_rows = kMaxWaves * kRowsPerWave;
+  pl->row_splits = (pl->R + max_rows - 1) / max_rows;
+  int per = (pl->R + pl->row_splits - 1) / pl->row_splits;
+  pl->rows_per_split = (per + kRowsPerWave - 1) / kRowsPerWave * kRowsPerWave;
+  pl->waves = pl->rows_per_split / kRowsPerWave;
+  pl->chunk_keys = chunk_keys_setting();
+  int64_t chunks = 0;
+  for (int r = 0; r < p->n_seqs; ++r) {
+    int n = p->cu_seqlens_host[r + 1] - p->cu_seqlens_host[r];
+    chunks += (n + pl->chunk_keys - 1) / pl->chunk_keys;
+  }
+  if (chunks > (1 << 30)) return CODECOMP_EINVAL_SHAPE;
+  pl->total_chunks = (int)chunks;
+
+  const int64_t d = pl->d;
+  pl->q_st = p->q_stride_tok ? p->q_stride_tok : d;
+  pl->q_sh = p->q_stride_head ? p->q_stride_head : (int64_t)pl->W * d;
+  pl->q_ss = p->q_stride_seq ? p->q_stride_seq : (int64_t)pl->Hq * pl->W * d;
+  pl->q_sl = p->q_stride_layer ? p->q_stride_layer : (int64_t)pl->n_seqs * pl->Hq * pl->W * d;
+  pl->kv_st = p->kv_stride_tok ? p->kv_stride_tok : d;
+  pl->kv_sh = p->kv_stride_head ? p->kv_stride_head : (int64_t)pl->T * d;
+  pl->kv_sl = p->kv_stride_layer ? p->kv_stride_layer : (int64_t)pl->Hkv * pl->T * d;
+  pl->o_st = p->out_stride_tok ? p->out_stride_tok : d;
+  pl->o_sh = p->out_stride_head ? p->out_stride_head : (int64_t)pl->TB * d;
+  pl->o_sl = p->out_stride_layer ? p->out_stride_layer : (int64_t)pl->Hkv * pl->TB * d;
+  if (pl->q_st < d || pl->kv_st < d || pl->o_st < d) return CODECOMP_EINVAL_SHAPE;
+  pl->cu_seqlens_dev = p->cu_seqlens_dev;
+  pl->cu_budgets_dev = p->cu_budgets_dev;
+
+  // workspace: per-chunk softmax statistics, merged row normalisers, raw attention mass
+  const size_t LH = (size_t)pl->L * pl->Hkv;
+  const size_t rpad = (size_t)pl->row_splits * pl->rows_per_split;
+  size_t off = 0;
+  pl->off_stats = off; off = align256(off + LH * pl->total_chunks * rpad * 2 * sizeof(float));
+  pl->off_lse = off;   off = align256(off + LH * pl->n_seqs * rpad * sizeof(float));
+  pl->off_uraw = off;  off = align256(off + (size_t)pl->row_splits * LH * pl->T * sizeof(float));
+  pl->ws_bytes = off;
+  return CODECOMP_OK;
+}
+
+static int check_ws(const Plan& pl, const void* ws, size_t bytes) {
+  if (!ws || ((uintptr_t)ws & 255) != 0 || bytes < pl.ws_bytes) return CODECOMP_EINVAL_WORKSPACE;
+  return CODECOMP_OK;
+}
+
+static bool misaligned16(const void* p) { return ((uintptr_t)p & 15) != 0; }
+
+}  // namespace codecomp
+
+using namespace codecomp;
+
+extern "C" {
+
+size_t codecomp_workspace_bytes(const codecomp_params* params) {
+  Plan pl;
+  if (make_plan(params, &pl) != CODECOMP_OK) return 0;
+  return pl.ws_bytes;
+}
+
+int codecomp_validate(const codecomp_params* params) {
+  Plan pl;
+  return make_plan(params, &pl);
+}
+
+int codecomp_score(const void* q_obs, const void* k, const float* prior, const codecomp_params* params,
+                   float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!q_obs || !k || !prior || !params || !scores) return CODECOMP_EINVAL_NULL;
+  Plan pl;
+  if (int rc = make_plan(params, &pl)) return rc;
+  if (misaligned16(q_obs) || misaligned16(k)) return CODECOMP_EINVAL_SHAPE;
+  if (int rc = check_ws(pl, workspace, workspace_bytes)) return rc;
+  return launch_score(pl, q_obs, k, prior, scores, workspace, (hipStream_t)hip_stream);
+}
+
+int codecomp_select(const float* scores, const codecomp_params* params, int32_t* idx, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+  if (!scores || !params || !idx) return CODECOMP_EINVAL_NULL;
+  Plan pl;
+  if (int rc = make_plan(params, &pl)) return rc;
+  if (int rc = check_ws(pl, workspace, workspace_bytes)) return rc;
+  return launch_select(pl, scores, idx, (hipStream_t)hip_stream);
+}
+
+int codecomp_gather(const void* k, const void* v, const int32_t* idx, const codecomp_params* params,
+                    void* k_out, void* v_out, void* hip_stream) {
+  if (!k || !v || !idx || !params || !k_out || !v_out) return CODECOMP_EINVAL_NULL;
+  Plan pl;
+  if (int rc = make_plan(params, &pl)) return rc;
+  if (misaligned16(k) || misaligned16(v) || misaligned16(k_out) || misaligned16(v_out)) return CODECOMP_EINVAL_SHAPE;
+  return launch_gather(pl, k, v, idx, k_out, v_out, (hipStream_t)hip_stream);
+}
+
+int codecomp_compress(const void* q_obs, const void* k, const void* v, const float* prior,
+                      const codecomp_params* params, float* scores, int32_t* idx, void* k_out, void* v_out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!q_obs || !k || !v || !prior || !params || !scores || !idx || !k_out || !v_out) return CODECOMP_EINVAL_NULL;
+  Plan pl;
+  if (int rc = make_plan(params, &pl)) return rc;
+  if (misaligned16(q_obs) || misaligned16(k) || misaligned16(v) || misaligned16(k_out) || misaligned16(v_out))
+    return CODECOMP_EINVAL_SHAPE;
+  if (int rc = check_ws(pl, workspace, workspace_bytes)) return rc;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (int rc = launch_score(pl, q_obs, k, prior, scores, workspace, s)) return rc;
+  if (int rc = launch_select(pl, scores, idx, s)) return rc;
+  return launch_gather(pl, k, v, idx, k_out, v_out, s);
+}
+
+const char* codecomp_status_string(int status) {
+  switch (status) {
+    case CODECOMP_OK: return "ok";
+    case CODECOMP_EINVAL_NULL: return "a required pointer is NULL";
+    case CODECOMP_EINVAL_SHAPE: return "bad shape, stride or alignment";
+    case CODECOMP_EINVAL_WINDOW: return "window must satisfy 1 <= W <= N_r for every request";
+    case CODECOMP_EINVAL_BUDGET: return "budget must satisfy W <= B_r <= N_r for every request";
+    case CODECOMP_EINVAL_POOL: return "pool_kernel must be odd and >= 1";
+    case CODECOMP_EINVAL_HEADS: return "n_q_heads must be a positive multiple of n_kv_heads";
+    case CODECOMP_EINVAL_HEADDIM: return "head_dim must be 64 or 128";
+    case CODECOMP_EINVAL_SEQLENS: return "cu_seqlens / cu_budgets must start at 0 and increase";
+    case CODECOMP_EINVAL_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
+    case CODECOMP_EINVAL_PRIOR: return "prior_weight / softmax_scale must be finite and >= 0";
+    default: return status > 0 ? "HIP runtime error (hipError_t value)" : "unknown status";
+  }
+}
+
+int codecomp_version(void) { return 100; }
+
+}  // extern "C"

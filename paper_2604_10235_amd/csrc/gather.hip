@@ -1,0 +1,81 @@
+// Gather step: copy the retained K and V rows into the compact per-layer cache (the
+// compressed chunk of section "Position Encoding": rows keep their original order).
+// Pure data movement: a row of d bf16 values is moved as d/8 16-byte pieces by consecutive
+// lanes, so both the reads and the writes of a row are one contiguous segment.
+#include "plan.h"
+
+namespace codecomp {
+
+struct GatherArgs {
+  const uint16_t* k;
+  const uint16_t* v;
+  const int32_t* idx;
+  const int32_t* cu_seqlens;
+  const int32_t* cu_budgets;
+  uint16_t* k_out;
+  uint16_t* v_out;
+  int n_seqs, Hkv, TB, pieces_log2;    // pieces per row = d / 8 (8 or 16)
+  int64_t kv_sl, kv_sh, kv_st, o_sl, o_sh, o_st;
+};
+
+constexpr int kGatherThreads = 256;
+constexpr int kGatherRowsPerThread = 4;
+
+__global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
+  const int pieces = 1 << a.pieces_log2;
+  const int rows_per_pass = kGatherThreads >> a.pieces_log2;
+  const int piece = threadIdx.x & (pieces - 1);
+  const int rsub = threadIdx.x >> a.pieces_log2;
+  const int lz = blockIdx.y;
+  const int layer = lz / a.Hkv, head = lz - layer * a.Hkv;
+  const int32_t* idx = a.idx + (int64_t)lz * a.TB;
+  const uint16_t* kb = a.k + layer * a.kv_sl + head * a.kv_sh;
+  const uint16_t* vb = a.v + layer * a.kv_sl + head * a.kv_sh;
+  uint16_t* ko = a.k_out + layer * a.o_sl + head * a.o_sh;
+  uint16_t* vo = a.v_out + layer * a.o_sl + head * a.o_sh;
+  const int slot0 = blockIdx.x * rows_per_pass * kGatherRowsPerThread + rsub;
+
+  uint4 kv[kGatherRowsPerThread], vv[kGatherRowsPerThread];
+#pragma unroll
+  for (int i = 0; i < kGatherRowsPerThread; ++i) {
+    const int slot = slot0 + i * rows_per_pass;
+    if (slot < a.TB) {
+      int lo = 0, hi = a.n_seqs;          // request owning this output slot
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (a.cu_budgets[mid] <= slot) lo = mid; else hi = mid;
+      }
+      // indices are clamped into the request so that a corrupt idx can never read out of bounds
+      const int s0 = a.cu_seqlens[lo], n = a.cu_seqlens[lo + 1] - s0;
+      const int64_t tok = (int64_t)s0 + min(max(idx[slot], 0), n - 1);
+      kv[i] = *reinterpret_cast<const uint4*>(kb + tok * a.kv_st + piece * 8);
+      vv[i] = *reinterpret_cast<const uint4*>(vb + tok * a.kv_st + piece * 8);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kGatherRowsPerThread; ++i) {
+    const int slot = slot0 + i * rows_per_pass;
+    if (slot < a.TB) {
+      *reinterpret_cast<uint4*>(ko + (int64_t)slot * a.o_st + piece * 8) = kv[i];
+      *reinterpret_cast<uint4*>(vo + (int64_t)slot * a.o_st + piece * 8) = vv[i];
+    }
+  }
+}
+
+int launch_gather(const Plan& pl, const void* k, const void* v, const int32_t* idx, void* k_out, void* v_out,
+                  hipStream_t stream) {
+  GatherArgs a;
+  a.k = static_cast<const uint16_t*>(k); a.v = static_cast<const uint16_t*>(v); a.idx = idx;
+  a.cu_seqlens = pl.cu_seqlens_dev; a.cu_budgets = pl.cu_budgets_dev;
+  a.k_out = static_cast<uint16_t*>(k_out); a.v_out = static_cast<uint16_t*>(v_out);
+  a.n_seqs = pl.n_seqs; a.Hkv = pl.Hkv; a.TB = pl.TB; a.pieces_log2 = pl.d == 128 ? 4 : 3;
+  a.kv_sl = pl.kv_sl; a.kv_sh = pl.kv_sh; a.kv_st = pl.kv_st;
+  a.o_sl = pl.o_sl; a.o_sh = pl.o_sh; a.o_st = pl.o_st;
+  const int rows_per_block = (kGatherThreads >> a.pieces_log2) * kGatherRowsPerThread;
+  gather_kernel<<<dim3((pl.TB + rows_per_block - 1) / rows_per_block, pl.L * pl.Hkv), dim3(kGatherThreads), 0,
+                  stream>>>(a);
+  if (hipError_t e = hipGetLastError()) return (int)e;
+  return 0;
+}
+
+}  // namespace codecomp

@@ -1,0 +1,45 @@
+// Host-side launch plan shared by the translation units of libcodecomp (internal header).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "codecomp.h"
+
+namespace codecomp {
+
+constexpr int kRowsPerWave = 64;      // query rows (window x group) owned by one wavefront
+constexpr int kMaxWaves = 8;          // wavefronts per workgroup in the score kernels
+constexpr int kTileKeys = 64;         // keys staged through LDS per pipeline step
+constexpr int kSelectThreads = 1024;  // one workgroup per (layer, head, request) in select
+
+struct Plan {
+  int L, Hq, Hkv, G, d, W, pool, n_seqs;
+  float lambda, scale;
+  int T, TB;                 // total tokens / total output slots over the packed requests
+  int max_n;                 // longest request
+  int R;                     // G * W softmax rows per (layer, KV head, request)
+  int row_splits;            // workgroups along the row axis (each <= kMaxWaves * kRowsPerWave rows)
+  int rows_per_split;        // multiple of kRowsPerWave
+  int waves;                 // rows_per_split / kRowsPerWave
+  int chunk_keys;            // keys handled by one workgroup of the score passes
+  int total_chunks;          // sum over requests of ceil(N_r / chunk_keys)
+  int64_t q_sl, q_ss, q_sh, q_st;
+  int64_t kv_sl, kv_sh, kv_st;
+  int64_t o_sl, o_sh, o_st;
+  const int32_t* cu_seqlens_dev;
+  const int32_t* cu_budgets_dev;
+  // workspace layout (byte offsets, each 256-byte aligned)
+  size_t off_stats, off_lse, off_uraw, ws_bytes;
+};
+
+// Validates `p` and fills `plan`.  Returns 0 or a CODECOMP_E* code.  Host only, no HIP calls.
+int make_plan(const codecomp_params* p, Plan* plan);
+
+int launch_score(const Plan& pl, const void* q, const void* k, const float* prior, float* scores,
+                 void* workspace, hipStream_t stream);
+int launch_select(const Plan& pl, const float* scores, int32_t* idx, hipStream_t stream);
+int launch_gather(const Plan& pl, const void* k, const void* v, const int32_t* idx, void* k_out, void* v_out,
+                  hipStream_t stream);
+
+}  // namespace codecomp

@@ -1,0 +1,147 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+from oracle import codecomp_oracle as orc
+from paper_2604_10235_amd import workloads as wl
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _binding():
+    from paper_2604_10235_amd import binding
+    return binding
+
+
+def run_case(w, *, fused=True, check_oracle=True):
+    """Runs the three steps (or the fused call) and compares every stage with the oracle."""
+    import torch
+    b = _binding()
+    q, k, v, prior = wl.make_all(w)
+    prob = b.DeviceProblem(w, q, k, v, prior)
+    if fused:
+        prob.compress()
+    else:
+        prob.score(); prob.select(); prob.gather()
+    torch.cuda.synchronize()
+    sc_gpu = prob.scores.cpu().numpy()
+    idx_gpu = prob.idx.cpu().numpy()
+    ko, vo = b.DeviceProblem.bits(prob.k_out), b.DeviceProblem.bits(prob.v_out)
+    cu, cb = w.cu_seqlens(), w.cu_budgets()
+
+    # gather: bit-exact against a host row copy with the GPU's own indices
+    assert np.array_equal(ko, pu.host_gather(k, idx_gpu, cu, cb))
+    assert np.array_equal(vo, pu.host_gather(v, idx_gpu, cu, cb))
+    # select: integer work, must equal the oracle's rule applied to the very same fp32 scores
+    idx_same = orc.select_packed(sc_gpu.astype(np.float64), cu, cb, w.window)
+    assert np.array_equal(idx_gpu.astype(np.int64), idx_same)
+    if not check_oracle:
+        return prob, sc_gpu, idx_gpu
+    # scores and index sets against the fp64 oracle
+    sc_ref = orc.score_packed(q, k, prior, cu, pool_kernel=w.pool_kernel, prior_weight=w.prior_weight)
+    pu.assert_scores_close(sc_gpu, sc_ref)
+    idx_ref = orc.select_packed(sc_ref, cu, cb, w.window)
+    for l in range(w.n_layers):
+        for h in range(w.n_kv_heads):
+            for r in range(w.n_seqs):
+                pu.assert_index_sets_match(idx_gpu[l, h, cb[r]:cb[r + 1]], idx_ref[l, h, cb[r]:cb[r + 1]],
+                                           sc_ref[l, h, cu[r]:cu[r + 1]], w.window, what=f"idx[{l},{h},{r}]")
+    return prob, sc_gpu, idx_gpu
+
+
+def test_tiny_config_full():
+    run_case(wl.tiny(), fused=False)
+    run_case(wl.tiny(), fused=True)
+
+
+def test_qwen_shape_ragged_tail():
+    # 5000 keys = 4 chunks of 1024 + 904 = 14 tiles of 64 + 8: several chunks, several tiles, ragged tail
+    run_case(wl.scaled(wl.qwen7b_32k(), n_layers=2, seqlens=[5000]))
+
+
+def test_llama_shape_with_drift():
+    w = wl.scaled(wl.llama8b_64k(), n_layers=2, seqlens=[3001], n_q_heads=8, n_kv_heads=2)
+    run_case(w)
+
+
+def test_long_shape_two_row_splits():
+    # W = 128, G = 7: 896 softmax rows -> two workgroups along the row axis
+    run_case(wl.scaled(wl.long_128k(), n_layers=1, seqlens=[4100], n_kv_heads=2, n_q_heads=14))
+
+
+def test_ragged_batch():
+    w = wl.scaled(wl.ragged_agentic(), seqlens=[700, 1300, 64, 2049, 1024, 65], budgets=[70, 130, 64, 204, 1024, 65])
+    run_case(w, fused=True)
+    run_case(w, fused=False)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(seqlens=[32], budgets=[32], window=32),                       # N == W == B: window only, no prefix
+    dict(seqlens=[1], budgets=[1], window=1),                          # a single token
+    dict(seqlens=[300], budgets=[300], window=16),                     # B == N: identity
+    dict(seqlens=[300], budgets=[16], window=16),                      # B == W: window only
+    dict(seqlens=[37], budgets=[20], window=5),                        # shorter than one tile, odd window
+    dict(seqlens=[1000], budgets=[100], window=40, n_q_heads=12),      # R = 3 * 40 = 120 rows, not a multiple of 32
+    dict(seqlens=[777], budgets=[99], window=32, pool_kernel=1),       # no pooling
+    dict(seqlens=[777], budgets=[99], window=32, prior_weight=0.0),    # attention only
+    dict(seqlens=[777], budgets=[99], window=32, pool_kernel=31),      # wide pooling
+    dict(seqlens=[1500], budgets=[200], window=32, head_dim=64, n_q_heads=8),   # d = 64 with a group of 2
+])
+def test_edge_cases(kw):
+    base = dict(n_layers=1, n_q_heads=4, n_kv_heads=4, head_dim=128)
+    base.update(kw)
+    run_case(wl.scaled(wl.qwen7b_32k(), **base))
+
+
+def test_zero_keys_closed_form():
+    # all keys equal (zero): every token gets mass W/N, pooled with zero padding (closed form, no oracle)
+    import torch
+    b = _binding()
+    w = wl.scaled(wl.qwen7b_32k(), n_layers=1, seqlens=[20000], prior_weight=0.0)
+    q, k, v, prior = wl.make_all(w)
+    k[:] = 0
+    prob = b.DeviceProblem(w, q, k, v, prior)
+    prob.score(); torch.cuda.synchronize()
+    sc = prob.scores.cpu().numpy().astype(np.float64)
+    n, W, kk = 20000, w.window, w.pool_kernel
+    expect = np.full(n, W / n)
+    for e in range(3):
+        expect[e] = expect[n - 1 - e] = (W / n) * (kk - 3 + e) / kk
+    np.testing.assert_allclose(sc, np.tile(expect, (1, w.n_kv_heads, 1)), rtol=1e-5)
+
+
+def test_deterministic_and_workspace_poison():
+    import torch
+    w = wl.scaled(wl.qwen7b_32k(), n_layers=2, seqlens=[3000, 1111], budgets=[300, 111])
+    prob, sc1, idx1 = run_case(w, check_oracle=False)
+    k1, v1 = prob.k_out.clone(), prob.v_out.clone()
+    prob.workspace.fill_(0xFF)            # NaN patterns: nothing may be read before it is written
+    prob.scores.fill_(float("nan")); prob.idx.fill_(-1); prob.k_out.fill_(0); prob.v_out.fill_(0)
+    prob.compress(); torch.cuda.synchronize()
+    assert np.array_equal(prob.scores.cpu().numpy(), sc1)
+    assert np.array_equal(prob.idx.cpu().numpy(), idx1)
+    assert torch.equal(prob.k_out, k1) and torch.equal(prob.v_out, v1)
+
+
+def test_strided_kv_and_output():
+    # K/V stored token-major ([T][H_kv][d], as a paged cache would) through the stride arguments
+    import torch
+    b = _binding()
+    w = wl.scaled(wl.qwen7b_32k(), n_layers=2, seqlens=[2100])
+    q, k, v, prior = wl.make_all(w)
+    ref = b.DeviceProblem(w, q, k, v, prior)
+    ref.compress(); torch.cuda.synchronize()
+    prob = b.DeviceProblem(w, q, k, v, prior)
+    L, H, T, d = k.shape
+    prob.k = ref.k.permute(0, 2, 1, 3).contiguous()      # [L][T][H][d]
+    prob.v = ref.v.permute(0, 2, 1, 3).contiguous()
+    prob.params.kv_stride_layer, prob.params.kv_stride_head, prob.params.kv_stride_tok = T * H * d, d, H * d
+    TB = w.total_budget
+    prob.k_out = torch.zeros((L, TB, H, d), dtype=torch.bfloat16, device="cuda:0")
+    prob.v_out = torch.zeros_like(prob.k_out)
+    prob.params.out_stride_layer, prob.params.out_stride_head, prob.params.out_stride_tok = TB * H * d, d, H * d
+    prob.compress(); torch.cuda.synchronize()
+    assert torch.equal(prob.scores, ref.scores) and torch.equal(prob.idx, ref.idx)
+    assert torch.equal(prob.k_out.permute(0, 2, 1, 3), ref.k_out)
+    assert torch.equal(prob.v_out.permute(0, 2, 1, 3), ref.v_out)
