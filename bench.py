@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the prefill KV-eviction hot path (score -> select -> gather) on one MI355X.
+
+One "step" is one fused codecomp_compress call over every layer of the workload: all layers
+scored, selected and gathered, inputs already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload qwen7b_32k]
+
+value = token-layers per second = (sum of request lengths) x layers / time per step.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def algorithmic_bytes(w) -> dict:
+    """Bytes the method itself must move per step: K once, Q, prior, scores written and read once,
+    indices written and read once, retained K and V rows read and written."""
+    L, H, T, TB, d = w.n_layers, w.n_kv_heads, w.total_tokens, w.total_budget, w.head_dim
+    b = {
+        "k_read": L * H * T * d * 2,
+        "q_read": L * w.n_seqs * w.n_q_heads * w.window * d * 2,
+        "prior_read": L * T * 4,
+        "scores_rw": 2 * L * H * T * 4,
+        "idx_rw": 2 * L * H * TB * 4,
+        "gather_rw": 2 * 2 * L * H * TB * d * 2,
+    }
+    b["total"] = sum(b.values())
+    return b
+
+
+def read_traffic(name: str):
+    """Measured HBM bytes per launch of the dominant kernel, from the committed counter summary
+    (profiles/pmc_<workload>.txt, lines `key = value`); None when no summary exists."""
+    path = os.path.join(ROOT, "profiles", f"pmc_{name}.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if "=" in line and not line.lstrip().startswith("#"):
+            k, v = line.split("=", 1)
+            try:
+                vals[k.strip()] = float(v.split()[0])
+            except ValueError:
+                pass
+    return vals or None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="qwen7b_32k")
+    ap.add_argument("--cpu-layers", type=int, default=12, help="layers the CPU oracle is timed and compared on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2604_10235_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU substitute", file=sys.stderr)
+        return 3
+    w = wl.CONFIGS[args.workload]()
+    t0 = time.time()
+    q, k, v, prior = wl.make_all(w, threads=min(16, os.cpu_count() or 8))
+    t_gen = time.time() - t0
+    prob = binding.DeviceProblem(w, q, k, v, prior)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        prob.compress()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        prob.compress()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-kernel durations: the same kernels enqueued one by one with events between them
+    names = ["score_row_stats", "score_row_merge", "score_mass", "score_finish", "select", "gather"]
+    stages = [binding.STAGE_ROW_STATS, binding.STAGE_ROW_MERGE, binding.STAGE_MASS, binding.STAGE_FINISH]
+    acc = dict.fromkeys(names, 0.0)
+    for _ in range(args.steps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)]
+        ev[0].record()
+        for i, st in enumerate(stages):
+            prob.score_stages(st)
+            ev[i + 1].record()
+        prob.select(); ev[5].record()
+        prob.gather(); ev[6].record()
+        torch.cuda.synchronize()
+        for i, nm in enumerate(names):
+            acc[nm] += ev[i].elapsed_time(ev[i + 1])
+    stage_ms = {nm: acc[nm] / args.steps for nm in names}
+
+    T, L = w.total_tokens, w.n_layers
+    value = T * L / (ms_per_step * 1e-3)
+    ab = algorithmic_bytes(w)
+    hbm_gbs = ab["total"] / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel: one of the two MFMA passes; flops of one launch = 2 * R * sum(N_r) * d per (layer, KV head)
+    dom = max(("score_row_stats", "score_mass"), key=lambda n: stage_ms[n])
+    flops = 2.0 * w.group * w.window * T * w.head_dim * w.n_kv_heads * L
+    achieved = flops / (stage_ms[dom] * 1e-3) / 1e12
+    traffic = read_traffic(w.name)
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                "traffic": None if not traffic else traffic.get(f"{dom}_hbm_bytes_per_launch"),
+                "kernel_ms": round(stage_ms[dom], 4), "flop_per_launch": flops}
+
+    out = {
+        "metric": "KV tokens scored+selected+gathered/sec per GPU; HBM GB/s as % of peak",
+        "value": round(value, 1), "unit": "token-layers/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "n_layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "tokens": T, "n_seqs": w.n_seqs, "window": w.window,
+                   "budget_total": w.total_budget, "pool_kernel": w.pool_kernel, "prior_weight": w.prior_weight},
+        "tokens_per_s_whole_model": round(T / (ms_per_step * 1e-3), 1),
+        "hbm": {"algorithmic_bytes": ab["total"], "gb_per_s": round(hbm_gbs, 1), "peak_gb_per_s": HBM_PEAK_GBS,
+                "frac_of_peak": round(hbm_gbs / HBM_PEAK_GBS, 4)},
+        "stage_ms": {k_: round(v_, 4) for k_, v_ in stage_ms.items()},
+        "stage_ms_sum": round(sum(stage_ms.values()), 4),
+        "roofline": roofline,
+        "input_generation_s": round(t_gen, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import codecomp_oracle as orc
+        from tests import parity_util as pu
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        nl = max(1, min(args.cpu_layers, L))
+        layers = sorted(set(np.linspace(0, L - 1, nl).round().astype(int).tolist()))   # always layer 0 and L-1
+        cu, cb = w.cu_seqlens(), w.cu_budgets()
+        t0 = time.perf_counter()
+        sc_ref, idx_ref, ko_ref, vo_ref = orc.compress_packed(q[layers], k[layers], v[layers], prior, cu, cb,
+                                                             window=w.window, pool_kernel=w.pool_kernel,
+                                                             prior_weight=w.prior_weight)
+        t_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(T * len(layers) / t_cpu, 1), "unit": "token-layers/s", "cores": cores,
+                               "kind": "oracle", "seconds": round(t_cpu, 2),
+                               "sample": f"{len(layers)} of {L} layers (all heads, all requests) of the same inputs"}
+        # parity report on the sampled layers (the GPU results are those of the timed fused call)
+        prob.compress(); torch.cuda.synchronize()
+        sc = prob.scores[layers].cpu().numpy()
+        idx = prob.idx[layers].cpu().numpy()
+        worst = pu.assert_scores_close(sc, sc_ref)
+        ndiff = 0
+        for li in range(len(layers)):
+            for h in range(w.n_kv_heads):
+                for r in range(w.n_seqs):
+                    ndiff += pu.assert_index_sets_match(idx[li, h, cb[r]:cb[r + 1]], idx_ref[li, h, cb[r]:cb[r + 1]],
+                                                        sc_ref[li, h, cu[r]:cu[r + 1]], w.window)
+        ko = binding.DeviceProblem.bits(prob.k_out[layers]); vo = binding.DeviceProblem.bits(prob.v_out[layers])
+        exact = bool(np.array_equal(ko, pu.host_gather(k[layers], idx, cu, cb)) and
+                     np.array_equal(vo, pu.host_gather(v[layers], idx, cu, cb)))
+        out["parity"] = {"layers_checked": len(layers), "max_rel_score_err": float(f"{worst:.3e}"),
+                         "tie_band_index_diffs": int(ndiff), "gather_bit_exact": exact}
+        if not exact:
+            print(json.dumps(out))
+            return 4
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

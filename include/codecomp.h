@@ -96,6 +96,22 @@ int codecomp_validate(const codecomp_params* params);
 int codecomp_score(const void* q_obs, const void* k, const float* prior, const codecomp_params* params,
                    float* scores, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The kernels of codecomp_score, selectable one by one (a bit mask of CODECOMP_STAGE_*), in the
+ * order row statistics -> row merge -> attention mass -> pool + prior.  Meant for per-kernel
+ * timing and stage-wise debugging: a later stage reads what the earlier ones left in `workspace`,
+ * so the stages of one problem must be enqueued in order with the same arguments.
+ * CODECOMP_STAGE_ALL is exactly codecomp_score. */
+enum {
+  CODECOMP_STAGE_ROW_STATS = 1,   /* pass 1: per-chunk (max, sum) of every softmax row             */
+  CODECOMP_STAGE_ROW_MERGE = 2,   /* log-sum-exp of every row over the chunks of its request       */
+  CODECOMP_STAGE_MASS = 4,        /* pass 2: u(j) = sum over rows of softmax probabilities, / G    */
+  CODECOMP_STAGE_FINISH = 8,      /* average pool + lambda * prior -> scores                       */
+  CODECOMP_STAGE_ALL = 15
+};
+int codecomp_score_stages(const void* q_obs, const void* k, const float* prior, const codecomp_params* params,
+                          float* scores, void* workspace, size_t workspace_bytes, unsigned stages,
+                          void* hip_stream);
+
 /* Per (layer, KV head, request): keep tokens N_r-W .. N_r-1, add the B_r - W tokens of the
  * prefix [0, N_r - W) with the largest scores (equal scores: the lower index wins; scores are
  * ordered as IEEE floats, -0 == +0, NaN unspecified), write the B_r indices in ascending

@@ -63,6 +63,9 @@ def lib() -> C.CDLL:
         l.codecomp_score.restype = C.c_int
         l.codecomp_score.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_size_t,
                                      C.c_void_p]
+        l.codecomp_score_stages.restype = C.c_int
+        l.codecomp_score_stages.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_size_t,
+                                            C.c_uint, C.c_void_p]
         l.codecomp_select.restype = C.c_int
         l.codecomp_select.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         l.codecomp_gather.restype = C.c_int
@@ -134,6 +137,15 @@ def codecomp_score(q_obs, k, prior, params, scores, workspace) -> None:
                                 workspace.numel() * workspace.element_size(), _stream()), "codecomp_score")
 
 
+STAGE_ROW_STATS, STAGE_ROW_MERGE, STAGE_MASS, STAGE_FINISH, STAGE_ALL = 1, 2, 4, 8, 15
+
+
+def codecomp_score_stages(q_obs, k, prior, params, scores, workspace, stages: int) -> None:
+    _check(lib().codecomp_score_stages(_ptr(q_obs), _ptr(k), _ptr(prior), C.byref(params), _ptr(scores),
+                                       _ptr(workspace), workspace.numel() * workspace.element_size(), int(stages),
+                                       _stream()), "codecomp_score_stages")
+
+
 def codecomp_select(scores, params, idx, workspace) -> None:
     _check(lib().codecomp_select(_ptr(scores), C.byref(params), _ptr(idx), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream()), "codecomp_select")
@@ -186,6 +198,9 @@ class DeviceProblem:
 
     def score(self):
         codecomp_score(self.q, self.k, self.prior, self.params, self.scores, self.workspace)
+
+    def score_stages(self, stages: int):
+        codecomp_score_stages(self.q, self.k, self.prior, self.params, self.scores, self.workspace, stages)
 
     def select(self):
         codecomp_select(self.scores, self.params, self.idx, self.workspace)

@@ -137,6 +137,18 @@ int codecomp_score(const void* q_obs, const void* k, const float* prior, const c
   return launch_score(pl, q_obs, k, prior, scores, workspace, (hipStream_t)hip_stream);
 }
 
+int codecomp_score_stages(const void* q_obs, const void* k, const float* prior, const codecomp_params* params,
+                          float* scores, void* workspace, size_t workspace_bytes, unsigned stages,
+                          void* hip_stream) {
+  if (!q_obs || !k || !prior || !params || !scores) return CODECOMP_EINVAL_NULL;
+  if (stages == 0 || (stages & ~(unsigned)CODECOMP_STAGE_ALL)) return CODECOMP_EINVAL_SHAPE;
+  Plan pl;
+  if (int rc = make_plan(params, &pl)) return rc;
+  if (misaligned16(q_obs) || misaligned16(k)) return CODECOMP_EINVAL_SHAPE;
+  if (int rc = check_ws(pl, workspace, workspace_bytes)) return rc;
+  return launch_score(pl, q_obs, k, prior, scores, workspace, (hipStream_t)hip_stream, stages);
+}
+
 int codecomp_select(const float* scores, const codecomp_params* params, int32_t* idx, void* workspace,
                     size_t workspace_bytes, void* hip_stream) {
   if (!scores || !params || !idx) return CODECOMP_EINVAL_NULL;

@@ -37,7 +37,7 @@ struct Plan {
 int make_plan(const codecomp_params* p, Plan* plan);
 
 int launch_score(const Plan& pl, const void* q, const void* k, const float* prior, float* scores,
-                 void* workspace, hipStream_t stream);
+                 void* workspace, hipStream_t stream, unsigned stages = CODECOMP_STAGE_ALL);
 int launch_select(const Plan& pl, const float* scores, int32_t* idx, hipStream_t stream);
 int launch_gather(const Plan& pl, const void* k, const void* v, const int32_t* idx, void* k_out, void* v_out,
                   hipStream_t stream);

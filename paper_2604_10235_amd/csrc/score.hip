@@ -298,36 +298,42 @@ __global__ __launch_bounds__(256) void score_finish_kernel(FinishArgs a) {
 }
 
 template <int D, int NW>
-static int launch_passes(const Plan& pl, const ScoreArgs& a, hipStream_t stream) {
+static int launch_passes(const Plan& pl, const ScoreArgs& a, hipStream_t stream, unsigned stages) {
   const dim3 grid(pl.total_chunks, pl.row_splits, pl.L * pl.Hkv);
   const dim3 block(NW * 64);
-  score_pass_kernel<D, NW, 1><<<grid, block, 0, stream>>>(a);
-  if (hipError_t e = hipGetLastError()) return (int)e;
-  const dim3 mgrid((a.rpad + 255) / 256, pl.n_seqs, pl.L * pl.Hkv);
-  score_merge_kernel<<<mgrid, dim3(256), 0, stream>>>(a);
-  if (hipError_t e = hipGetLastError()) return (int)e;
-  score_pass_kernel<D, NW, 2><<<grid, block, 0, stream>>>(a);
-  if (hipError_t e = hipGetLastError()) return (int)e;
+  if (stages & CODECOMP_STAGE_ROW_STATS) {
+    score_pass_kernel<D, NW, 1><<<grid, block, 0, stream>>>(a);
+    if (hipError_t e = hipGetLastError()) return (int)e;
+  }
+  if (stages & CODECOMP_STAGE_ROW_MERGE) {
+    const dim3 mgrid((a.rpad + 255) / 256, pl.n_seqs, pl.L * pl.Hkv);
+    score_merge_kernel<<<mgrid, dim3(256), 0, stream>>>(a);
+    if (hipError_t e = hipGetLastError()) return (int)e;
+  }
+  if (stages & CODECOMP_STAGE_MASS) {
+    score_pass_kernel<D, NW, 2><<<grid, block, 0, stream>>>(a);
+    if (hipError_t e = hipGetLastError()) return (int)e;
+  }
   return 0;
 }
 
 template <int D>
-static int dispatch_waves(const Plan& pl, const ScoreArgs& a, hipStream_t s) {
+static int dispatch_waves(const Plan& pl, const ScoreArgs& a, hipStream_t s, unsigned st) {
   switch (pl.waves) {
-    case 1: return launch_passes<D, 1>(pl, a, s);
-    case 2: return launch_passes<D, 2>(pl, a, s);
-    case 3: return launch_passes<D, 3>(pl, a, s);
-    case 4: return launch_passes<D, 4>(pl, a, s);
-    case 5: return launch_passes<D, 5>(pl, a, s);
-    case 6: return launch_passes<D, 6>(pl, a, s);
-    case 7: return launch_passes<D, 7>(pl, a, s);
-    case 8: return launch_passes<D, 8>(pl, a, s);
+    case 1: return launch_passes<D, 1>(pl, a, s, st);
+    case 2: return launch_passes<D, 2>(pl, a, s, st);
+    case 3: return launch_passes<D, 3>(pl, a, s, st);
+    case 4: return launch_passes<D, 4>(pl, a, s, st);
+    case 5: return launch_passes<D, 5>(pl, a, s, st);
+    case 6: return launch_passes<D, 6>(pl, a, s, st);
+    case 7: return launch_passes<D, 7>(pl, a, s, st);
+    case 8: return launch_passes<D, 8>(pl, a, s, st);
   }
   return CODECOMP_EINVAL_SHAPE;
 }
 
 int launch_score(const Plan& pl, const void* q, const void* k, const float* prior, float* scores,
-                 void* workspace, hipStream_t stream) {
+                 void* workspace, hipStream_t stream, unsigned stages) {
   char* ws = static_cast<char*>(workspace);
   ScoreArgs a;
   a.q = static_cast<const uint16_t*>(q);
@@ -343,8 +349,9 @@ int launch_score(const Plan& pl, const void* q, const void* k, const float* prio
   a.kv_sl = pl.kv_sl; a.kv_sh = pl.kv_sh; a.kv_st = pl.kv_st;
   a.c = pl.scale * 1.4426950408889634f;
   a.inv_g = 1.0f / (float)pl.G;
-  int rc = pl.d == 128 ? dispatch_waves<128>(pl, a, stream) : dispatch_waves<64>(pl, a, stream);
+  int rc = pl.d == 128 ? dispatch_waves<128>(pl, a, stream, stages) : dispatch_waves<64>(pl, a, stream, stages);
   if (rc) return rc;
+  if (!(stages & CODECOMP_STAGE_FINISH)) return 0;
 
   FinishArgs f;
   f.uraw = a.uraw; f.prior = prior; f.cu_seqlens = pl.cu_seqlens_dev; f.scores = scores;

@@ -1,0 +1,132 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+public header declares, and rejects bad arguments with the documented codes before any launch."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2604_10235_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def built():
+    if not os.path.exists(b.LIB_PATH):
+        from paper_2604_10235_amd import build
+        build.build_library(verbose=False)
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "codecomp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(codecomp_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert {"codecomp_score", "codecomp_select", "codecomp_gather", "codecomp_compress",
+            "codecomp_workspace_bytes", "codecomp_validate", "codecomp_status_string", "codecomp_version",
+            "codecomp_score_stages"} <= set(names)
+    lib = b.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_layout_matches_header():
+    # 10 x 4-byte fields, 4 pointers, 10 x int64 strides
+    assert C.sizeof(b.codecomp_params) == 40 + 32 + 80
+    assert b.codecomp_params.cu_seqlens_host.offset == 40
+    assert b.codecomp_params.q_stride_layer.offset == 72
+
+
+def good(**over):
+    kw = dict(n_layers=2, n_q_heads=8, n_kv_heads=2, head_dim=128, window=16, pool_kernel=7, prior_weight=1.0,
+              cu_seqlens_host=np.array([0, 100, 300]), cu_budgets_host=np.array([0, 20, 60]),
+              cu_seqlens_dev=0x1000, cu_budgets_dev=0x2000)
+    kw.update(over)
+    return b.make_params(**kw)
+
+
+def test_valid_params_and_workspace_size():
+    p = good()
+    assert b.codecomp_validate(p) == 0
+    ws = b.codecomp_workspace_bytes(p)
+    assert ws > 0 and ws % 256 == 0
+    # the raw attention mass alone needs L * H_kv * T floats
+    assert ws >= 2 * 2 * 300 * 4
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(n_layers=0), -2),
+    (dict(n_q_heads=7), -6),
+    (dict(n_kv_heads=0), -6),
+    (dict(head_dim=96), -7),
+    (dict(pool_kernel=4), -5),
+    (dict(pool_kernel=0), -5),
+    (dict(prior_weight=-1.0), -10),
+    (dict(prior_weight=float("nan")), -10),
+    (dict(softmax_scale=-0.5), -10),
+    (dict(window=0), -3),
+    (dict(window=101), -3),                                         # W > N_0 = 100
+    (dict(cu_budgets_host=np.array([0, 10, 60])), -4),              # B_0 = 10 < W
+    (dict(cu_budgets_host=np.array([0, 101, 141])), -4),            # B_0 > N_0
+    (dict(cu_seqlens_host=np.array([1, 100, 300])), -8),
+    (dict(cu_seqlens_host=np.array([0, 100, 100])), -8),            # empty request
+    (dict(cu_seqlens_dev=0), -1),
+    (dict(kv_stride_tok=100), -2),                                  # not a multiple of 8 elements
+    (dict(kv_stride_tok=64), -2),                                   # rows would overlap
+])
+def test_rejected_parameters(over, code):
+    p = good(**over)
+    assert b.codecomp_validate(p) == code
+    assert b.codecomp_workspace_bytes(p) == 0
+    assert b.status_string(code)
+
+
+def test_launching_calls_validate_before_touching_a_gpu():
+    # fake, well-aligned, non-null "device" pointers: every call must fail in validation, nothing is launched
+    lib = b.lib()
+    fake = 0x10000
+    p = good(head_dim=96)
+    assert lib.codecomp_score(fake, fake, fake, C.byref(p), fake, fake, 1 << 30, None) == -7
+    assert lib.codecomp_select(fake, C.byref(p), fake, fake, 1 << 30, None) == -7
+    assert lib.codecomp_gather(fake, fake, fake, C.byref(p), fake, fake, None) == -7
+    assert lib.codecomp_compress(fake, fake, fake, fake, C.byref(p), fake, fake, fake, fake, fake, 1 << 30, None) == -7
+    p = good()
+    assert lib.codecomp_score(None, fake, fake, C.byref(p), fake, fake, 1 << 30, None) == -1
+    assert lib.codecomp_score(fake, fake, fake, C.byref(p), fake, fake, 16, None) == -9       # workspace too small
+    assert lib.codecomp_score(fake, fake, fake, C.byref(p), fake, fake + 8, 1 << 30, None) == -9  # misaligned
+    assert lib.codecomp_score(fake + 2, fake, fake, C.byref(p), fake, fake, 1 << 30, None) == -2  # q not 16-byte aligned
+    assert lib.codecomp_score_stages(fake, fake, fake, C.byref(p), fake, fake, 1 << 30, 0, None) == -2
+    assert lib.codecomp_score_stages(fake, fake, fake, C.byref(p), fake, fake, 1 << 30, 16, None) == -2
+    assert lib.codecomp_compress(fake, fake, None, fake, C.byref(p), fake, fake, fake, fake, fake, 1 << 30, None) == -1
+
+
+def test_binding_raises_with_status_text():
+    with pytest.raises(b.CodecompError) as e:
+        b._check(-4, "codecomp_select")
+    assert "BUDGET" in str(e.value)
+
+
+def test_workload_recipes():
+    from paper_2604_10235_amd import workloads as wl
+    for name, mk in wl.CONFIGS.items():
+        w = mk()
+        assert all(w.window <= bb <= n for bb, n in zip(w.budgets, w.seqlens)), name
+    w = wl.ragged_agentic()
+    assert w.n_seqs == 16 and all(8192 <= n <= 49152 for n in w.seqlens)
+    assert all(bb == int(0.08 * n) for bb, n in zip(w.budgets, w.seqlens))
+    t = wl.tiny()
+    q, k, v, prior = wl.make_all(t)
+    assert q.shape == (1, 1, 4, 32, 64) and k.shape == (1, 4, 2048, 64) and prior.shape == (2048,)
+    assert set(np.unique(prior)) == {0.0, 1.0}
+    q2, k2, _, prior2 = wl.make_all(t)
+    assert np.array_equal(k, k2) and np.array_equal(q, q2) and np.array_equal(prior, prior2)   # seeded
+    # bf16 rounding is round-to-nearest-even
+    x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.140625], dtype=np.float32)
+    import torch
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(wl.f32_to_bf16_bits(x), ref)
