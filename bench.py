@@ -65,6 +65,7 @@ def main() -> int:
     ap.add_argument("--workload", default="qwen7b_32k")
     ap.add_argument("--cpu-layers", type=int, default=12, help="layers the CPU oracle is timed and compared on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (experiments only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -78,6 +79,8 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU substitute", file=sys.stderr)
         return 3
     w = wl.CONFIGS[args.workload]()
+    if args.layers > 0:
+        w = wl.scaled(w, name=f"{w.name}_L{args.layers}", n_layers=args.layers)
     t0 = time.time()
     q, k, v, prior = wl.make_all(w, threads=min(16, os.cpu_count() or 8))
     t_gen = time.time() - t0

@@ -14,7 +14,8 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libcodecomp.so")
+# CODECOMP_LIB selects another build of the same library (experiments); the default is the in-tree one
+LIB_PATH = os.environ.get("CODECOMP_LIB") or os.path.join(_HERE, "libcodecomp.so")
 
 STATUS = {
     0: "CODECOMP_OK", -1: "CODECOMP_EINVAL_NULL", -2: "CODECOMP_EINVAL_SHAPE", -3: "CODECOMP_EINVAL_WINDOW",

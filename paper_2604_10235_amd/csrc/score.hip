@@ -13,12 +13,16 @@
 // per tile).  v_mfma_f32_32x32x16_bf16: the A and B fragments have the same lane layout
 // (lane%32 = row/column, lane/32 = which 8 of the 16 k values), so swapping the operands
 // transposes the output tile without touching the loads.
+#include <type_traits>
+
 #include "plan.h"
 
 namespace codecomp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// 16-byte register quantum for loads/stores and MFMA fragments (a native vector: plain loads, no struct copies)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 struct ScoreArgs {
   const uint16_t* q;
@@ -35,7 +39,7 @@ struct ScoreArgs {
 
 #define NEG_BIG (-1.0e30f)
 
-__device__ __forceinline__ bf16x8 frag(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ bf16x8 frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ bool locate_chunk(const int32_t* cu, int n_seqs, int chunk_keys, int item,
                                              int& seq, int& tok0, int& n, int& local, int& chunk_base) {
@@ -52,6 +56,16 @@ __device__ __forceinline__ bool locate_chunk(const int32_t* cu, int n_seqs, int 
   return false;
 }
 
+// MFMA helper: D = A * B + C on one 32x32x16 bf16 step.  PASS 1 puts the keys on the A side
+// (output lane = query row), PASS 2 the queries (output lane = key).
+template <int PASS>
+__device__ __forceinline__ f32x16 mma_step(u32x4 qfrag, u32x4 kfrag, f32x16 acc) {
+  if constexpr (PASS == 1)
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(kfrag), frag(qfrag), acc, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(qfrag), frag(kfrag), acc, 0, 0, 0);
+}
+
 template <int D, int NW, int PASS>
 __global__ __launch_bounds__(NW * 64) void score_pass_kernel(ScoreArgs a) {
   constexpr int NT = NW * 64;
@@ -60,9 +74,12 @@ __global__ __launch_bounds__(NW * 64) void score_pass_kernel(ScoreArgs a) {
   constexpr int CH_PER_ROW = D / 8;            // 16-byte pieces per key row
   constexpr int NCH = kTileKeys * CH_PER_ROW;  // pieces per tile
   constexpr int LD = (NCH + NT - 1) / NT;      // pieces staged per thread
+  constexpr int LDS_ROWS = LD * NT / CH_PER_ROW;   // >= kTileKeys: rows past the tile are staging slack, never read
+  static_assert(LDS_ROWS >= kTileKeys, "tile staging");
 
-  __shared__ __attribute__((aligned(16))) unsigned char ktile[2][kTileKeys * ROWB];
-  __shared__ float colbuf[PASS == 2 ? 2 : 1][PASS == 2 ? NW : 1][kTileKeys];
+  __shared__ __attribute__((aligned(16))) unsigned char ktile[2][LDS_ROWS * ROWB];
+  // pass 2: column partials of the last four tiles, one row per (wave, half wave)
+  __shared__ float colbuf[PASS == 2 ? 4 : 1][PASS == 2 ? NW * 2 : 1][kTileKeys];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -79,10 +96,11 @@ __global__ __launch_bounds__(NW * 64) void score_pass_kernel(ScoreArgs a) {
   const int kstart = local * a.chunk_keys;
   const int kend = min(n, kstart + a.chunk_keys);
   const int ntiles = (kend - kstart + kTileKeys - 1) / kTileKeys;
+  const int rem = (kend - kstart) & (kTileKeys - 1);        // keys of a partial last tile (0 = it is full)
 
   // ---- this wave's 64 query rows as MFMA fragments
   const int row0 = split * a.rows_per_split + wave * kRowsPerWave;
-  uint4 qf[2][KS];
+  u32x4 qf[2][KS];
   {
     const uint16_t* qb = a.q + (int64_t)layer * a.q_sl + (int64_t)seq * a.q_ss;
 #pragma unroll
@@ -94,40 +112,36 @@ __global__ __launch_bounds__(NW * 64) void score_pass_kernel(ScoreArgs a) {
       const uint16_t* p = qb + (int64_t)(head * a.G + g) * a.q_sh + (int64_t)t * a.q_st + hf * 8;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (ok) v = *reinterpret_cast<const uint4*>(p + ks * 16);
+        u32x4 v = *reinterpret_cast<const u32x4*>(p + ks * 16);     // row 0 of the group when !ok: in bounds
+        if (!ok) v = u32x4{0, 0, 0, 0};
         qf[rb][ks] = v;
       }
     }
   }
 
+  // ---- K tile staging: global -> registers -> LDS.  Rows past the end of the chunk re-read its
+  // last key (always in bounds); such columns are masked (pass 1) or never stored (pass 2).
   const uint16_t* kb = a.k + (int64_t)layer * a.kv_sl + (int64_t)head * a.kv_sh + (int64_t)tok0 * a.kv_st;
-  uint4 stage[LD];
-  auto gload = [&](int key0) {
-#pragma unroll
-    for (int i = 0; i < LD; ++i) {
-      const int cidx = tid + i * NT;
-      const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;
-      const int key = key0 + row;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (cidx < NCH && key < kend) v = *reinterpret_cast<const uint4*>(kb + (int64_t)key * a.kv_st + col * 8);
-      stage[i] = v;
-    }
-  };
-  auto sstore = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < LD; ++i) {
-      const int cidx = tid + i * NT;
-      const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;
-      if (cidx < NCH) *reinterpret_cast<uint4*>(&ktile[buf][row * ROWB + col * 16]) = stage[i];
-    }
-  };
+  u32x4 stage[LD];
+#define CODECOMP_GLOAD(KEY0)                                                                        \
+  _Pragma("unroll") for (int i = 0; i < LD; ++i) {                                                  \
+    const int cidx = tid + i * NT;                                                                  \
+    const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;                               \
+    const int key = min((KEY0) + row, kend - 1);                                                    \
+    stage[i] = *reinterpret_cast<const u32x4*>(kb + (int64_t)key * a.kv_st + col * 8);              \
+  }
+#define CODECOMP_SSTORE(BUF)                                                                        \
+  _Pragma("unroll") for (int i = 0; i < LD; ++i) {                                                  \
+    const int cidx = tid + i * NT;                                                                  \
+    const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;                               \
+    *reinterpret_cast<u32x4*>(&ktile[BUF][row * ROWB + col * 16]) = stage[i];                       \
+  }
 
   const float c = a.c;
 
   // pass 1 state: running (max, sum) of this lane's row over the keys this lane sees
-  float m_run[2] = {NEG_BIG, NEG_BIG};
-  float l_run[2] = {0.f, 0.f};
+  float m_run0 = NEG_BIG, m_run1 = NEG_BIG;
+  float l_run0 = 0.f, l_run1 = 0.f;
   // pass 2 state: -lse of the 32 rows this lane holds in the S tile
   float nl[2][16];
   if constexpr (PASS == 2) {
@@ -137,108 +151,213 @@ __global__ __launch_bounds__(NW * 64) void score_pass_kernel(ScoreArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = row0 + rb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-        nl[rb][v] = row < a.R ? -lse[row] : -INFINITY;
+        const float x = lse[row];                 // row < rpad: in bounds; padding rows get no weight
+        nl[rb][v] = row < a.R ? -x : -INFINITY;
       }
   }
 
-  auto reduce_cols = [&](int buf, int key0) {
-    // sum the per-wave column partials of one finished tile and store the attention mass
+  // Sum the per-wave column partials of one finished tile and store the attention mass (pass 2).
+  auto reduce_cols = [&](int tile) __attribute__((always_inline)) {
     if constexpr (PASS == 2) {
-      if (tid < kTileKeys) {
+      if (tile >= 0 && tid < kTileKeys) {
         float s = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) s += colbuf[buf][w][tid];
-        const int key = key0 + tid;
+        for (int w = 0; w < NW * 2; ++w) s += colbuf[tile & 3][w][tid];
+        const int key = kstart + tile * kTileKeys + tid;
         if (key < kend) a.uraw[((int64_t)split * gridDim.z + lz) * a.T + tok0 + key] = s * a.inv_g;
       }
     }
   };
 
-  gload(kstart);
-  sstore(0);
-  __syncthreads();
+  // ------------------------------------------------------------------------------------------
+  // Software pipeline.  A tile (64 keys) is two sub-tiles (32 keys) a, b; each sub-tile is one
+  // "phase" of 2*KS MFMAs.  While the matrix core forms the logits of one sub-tile, the VALU does
+  // the softmax arithmetic on the previous one, cut into one slice per MFMA ("micro-step"); a
+  // scheduling fence after every micro-step keeps the compiler from regrouping them.  The K
+  // fragments of the next four k-steps are prefetched from LDS into a 4-entry register ring, the
+  // next tile travels global -> registers -> LDS one tile ahead, and the only workgroup barrier
+  // of a tile sits in the middle of phase b, where the first fragment of the next tile is needed.
+  // Global loads stay in flight across that barrier (it waits for LDS traffic only).
+  // ------------------------------------------------------------------------------------------
+  constexpr int MS = 2 * KS;                    // micro-steps (MFMAs) per phase
+  constexpr int RING = 4;                       // K fragments prefetched ahead
+  constexpr int BAR_KS = KS - RING;             // k-step of phase b before which the barrier sits
+  static_assert(KS >= RING, "fragment ring");
 
-  for (int t = 0; t < ntiles; ++t) {
-    const int buf = t & 1;
-    const int key0 = kstart + t * kTileKeys;
-    if (t + 1 < ntiles) gload(key0 + kTileKeys);
-    if constexpr (PASS == 2) {
-      if (t > 0) reduce_cols(buf ^ 1, key0 - kTileKeys);
-    }
-    const int nvalid = min(kTileKeys, kend - key0);
+  f32x16 accA0, accA1, accB0, accB1;
+  // the first phase consumes a sub-tile that does not exist: -inf logits add nothing to any sum
+#pragma unroll
+  for (int v = 0; v < 16; ++v) { accB0[v] = -INFINITY; accB1[v] = -INFINITY; }
+  u32x4 ring[RING];
 
+  auto kfrag_ptr = [&](int buf, int kh, int ks) __attribute__((always_inline)) {
+    return reinterpret_cast<const u32x4*>(&ktile[buf][(kh * 32 + l32) * ROWB + hf * 16 + ks * 32]);
+  };
+  auto lds_barrier = [&]() __attribute__((always_inline)) {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  };
+  // pass 1 only: logits of keys past the end of the chunk must not enter any row sum
+  auto mask_tail = [&](f32x16& x0, f32x16& x1, int kh) __attribute__((always_inline)) {
+    if constexpr (PASS == 1) {
 #pragma unroll
-    for (int kh = 0; kh < 2; ++kh) {
-      f32x16 acc0 = {0}, acc1 = {0};
-      const unsigned char* kp = &ktile[buf][(kh * 32 + l32) * ROWB + hf * 16];
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const uint4 kf = *reinterpret_cast<const uint4*>(kp + ks * 32);
-        if constexpr (PASS == 1) {
-          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(kf), frag(qf[0][ks]), acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(kf), frag(qf[1][ks]), acc1, 0, 0, 0);
-        } else {
-          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(qf[0][ks]), frag(kf), acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(qf[1][ks]), frag(kf), acc1, 0, 0, 0);
-        }
+      for (int v = 0; v < 16; ++v) {
+        const int key_local = kh * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+        if (key_local >= rem) { x0[v] = -INFINITY; x1[v] = -INFINITY; }
       }
+    }
+  };
+
+  // Softmax state of the sub-tile being consumed.
+  float s0, s1, mc0, mc1, al0, al1, mn0, mn1, t0, t1;
+  // pass 1 spends the first quarter of the micro-steps on the row maxima, the rest on the exponentials
+  constexpr int MAXSTEPS = PASS == 1 ? MS / 4 : 0;
+  constexpr int EXPSTEPS = MS - MAXSTEPS;
+  constexpr int EBASE = 32 / EXPSTEPS, EEXTRA = 32 % EXPSTEPS;
+
+  // One micro-step of softmax work on the finished sub-tile (p0, p1).
+  auto soft_step = [&](const f32x16& p0, const f32x16& p1, int m) __attribute__((always_inline)) {
+    if (m == 0) { s0 = 0.f; s1 = 0.f; }
+    if constexpr (PASS == 1) {
+      if (m < MAXSTEPS) {
+        constexpr int PER = 16 / MAXSTEPS;      // logits of each row block folded into the maxima per step
+        if (m == 0) { t0 = m_run0; t1 = m_run1; }
+#pragma unroll
+        for (int e = 0; e < PER; e += 2) {
+          t0 = fmaxf(fmaxf(t0, p0[m * PER + e]), p0[m * PER + e + 1]);
+          t1 = fmaxf(fmaxf(t1, p1[m * PER + e]), p1[m * PER + e + 1]);
+        }
+        if (m == MAXSTEPS - 1) {
+          mn0 = t0; mn1 = t1;
+          al0 = __builtin_amdgcn_exp2f((m_run0 - mn0) * c);
+          al1 = __builtin_amdgcn_exp2f((m_run1 - mn1) * c);
+          mc0 = mn0 * c; mc1 = mn1 * c;
+        }
+        return;
+      }
+    }
+    const int x = m - MAXSTEPS;
+    const int e0 = x * EBASE + (x < EEXTRA ? x : EEXTRA);
+    const int cnt = EBASE + (x < EEXTRA ? 1 : 0);
+#pragma unroll
+    for (int e = e0; e < e0 + cnt; ++e) {
+      const int v = e >> 1;
       if constexpr (PASS == 1) {
-        // lane = query row (l32 of row block rb); register v = key 8*(v/4) + 4*hf + v%4 of this half tile
-        if (nvalid < kTileKeys) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int key_local = kh * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-            if (key_local >= nvalid) { acc0[v] = -INFINITY; acc1[v] = -INFINITY; }
-          }
-        }
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-          const f32x16& acc = rb == 0 ? acc0 : acc1;
-          float tmax = acc[0];
-#pragma unroll
-          for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[v]);
-          const float m_new = fmaxf(m_run[rb], tmax);
-          const float alpha = __builtin_amdgcn_exp2f((m_run[rb] - m_new) * c);
-          const float mc = m_new * c;
-          float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-          for (int v = 0; v < 16; v += 2) {
-            s0 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v], c, -mc));
-            s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v + 1], c, -mc));
-          }
-          l_run[rb] = l_run[rb] * alpha + (s0 + s1);
-          m_run[rb] = m_new;
-        }
+        if (e & 1) s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(p1[v], c, -mc1));
+        else s0 += __builtin_amdgcn_exp2f(__builtin_fmaf(p0[v], c, -mc0));
       } else {
-        // lane = key l32 of this half tile; register v of row block rb = query row 8*(v/4) + 4*hf + v%4
-        float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          s0 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc0[v], c, nl[0][v]));
-          s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc1[v], c, nl[1][v]));
-        }
-        float col = s0 + s1;
-        col += __shfl_xor(col, 32);
-        if (lane < 32) colbuf[buf][wave][kh * 32 + lane] = col;
+        if (e & 1) s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(p1[v], c, nl[1][v]));
+        else s0 += __builtin_amdgcn_exp2f(__builtin_fmaf(p0[v], c, nl[0][v]));
       }
     }
+  };
+  auto soft_end = [&](int ptile, int pkh) __attribute__((always_inline)) {
+    if constexpr (PASS == 1) {
+      l_run0 = l_run0 * al0 + s0; l_run1 = l_run1 * al1 + s1;
+      m_run0 = mn0; m_run1 = mn1;
+    } else {
+      colbuf[ptile & 3][wave * 2 + hf][pkh * 32 + l32] = s0 + s1;
+    }
+  };
 
-    if (t + 1 < ntiles) sstore(buf ^ 1);
-    __syncthreads();
+  // Scheduling pattern of one phase for the machine scheduler: per MFMA, the share of softmax work
+  // that hides behind it (pass 1: maxima in the first quarter of the phase, exponentials after).
+  constexpr int SG_MAX = PASS == 1 ? 16 / (MAXSTEPS > 0 ? MAXSTEPS : 1) + 2 : 1;   // max3 ops (+ scalars) per step
+  constexpr int SG_E = (32 + EXPSTEPS - 1) / EXPSTEPS;                             // logits per exponential step
+  auto sched_phase = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int m = 0; m < MS; ++m) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one MFMA
+      if (m & 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);         // the ring refill (LDS read)
+      if (PASS == 1 && m < MAXSTEPS) {
+        __builtin_amdgcn_sched_group_barrier(0x002, SG_MAX, 0);             // max3 chain (+ scalars)
+      } else {
+        __builtin_amdgcn_sched_group_barrier(0x002, SG_E, 0);               // fma
+        __builtin_amdgcn_sched_group_barrier(0x400, SG_E, 0);               // exp2
+        __builtin_amdgcn_sched_group_barrier(0x002, SG_E, 0);               // add
+      }
+    }
+  };
+
+  // One tile = phase a + phase b.  MASKED (last, partial tile only) clears the logits of keys past
+  // the end of the chunk before they are consumed.
+  auto tile_body = [&](int t, auto masked) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked)::value;
+    const int buf = t & 1;
+    const f32x16 zero = {0};
+    // ---------------- phase a: logits of sub-tile a -> accA; softmax of accB (tile t-1, sub-tile b)
+    // tile t+1 waits in the staging registers: park it in the other LDS buffer (its last readers
+    // passed the previous barrier), then send the loads of tile t+2 on their way
+#ifndef CODECOMP_EXP_NO_SSTORE
+    CODECOMP_SSTORE(buf ^ 1)
+#endif
+#ifndef CODECOMP_EXP_NO_GLOAD
+    CODECOMP_GLOAD(kstart + (t + 2) * kTileKeys)
+#endif
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      accA0 = mma_step<PASS>(qf[0][ks], ring[ks % RING], ks == 0 ? zero : accA0);
+      soft_step(accB0, accB1, 2 * ks);
+      accA1 = mma_step<PASS>(qf[1][ks], ring[ks % RING], ks == 0 ? zero : accA1);
+      ring[ks % RING] = ks + RING < KS ? *kfrag_ptr(buf, 0, ks + RING) : *kfrag_ptr(buf, 1, ks + RING - KS);
+      soft_step(accB0, accB1, 2 * ks + 1);
+    }
+    soft_end(t - 1, 1);
+    sched_phase();
+    if constexpr (MASKED) mask_tail(accA0, accA1, 0);
+    // ---------------- phase b: logits of sub-tile b -> accB; softmax of accA (tile t, sub-tile a)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks == BAR_KS) lds_barrier();          // tile t+1 is now complete in LDS buffer buf^1
+      accB0 = mma_step<PASS>(qf[0][ks], ring[ks % RING], ks == 0 ? zero : accB0);
+      soft_step(accA0, accA1, 2 * ks);
+      accB1 = mma_step<PASS>(qf[1][ks], ring[ks % RING], ks == 0 ? zero : accB1);
+      ring[ks % RING] = ks + RING < KS ? *kfrag_ptr(buf, 1, ks + RING) : *kfrag_ptr(buf ^ 1, 0, ks + RING - KS);
+      soft_step(accA0, accA1, 2 * ks + 1);
+    }
+    soft_end(t, 0);
+    sched_phase();
+    if constexpr (MASKED) mask_tail(accB0, accB1, 1);
+  };
+
+  // ---- prologue: tile 0 into LDS buffer 0, tile 1 into the staging registers, first fragments
+  CODECOMP_GLOAD(kstart)
+  CODECOMP_SSTORE(0)
+  CODECOMP_GLOAD(kstart + kTileKeys)
+  lds_barrier();
+#pragma unroll
+  for (int r = 0; r < RING; ++r) ring[r] = *kfrag_ptr(0, 0, r);
+
+  const int nplain = rem != 0 ? ntiles - 1 : ntiles;
+  for (int t = 0; t < nplain; ++t) {
+#ifndef CODECOMP_EXP_NO_REDUCE
+    reduce_cols(t - 2);
+#endif
+    tile_body(t, std::false_type{});
+  }
+  if (rem != 0) {
+    reduce_cols(ntiles - 3);
+    tile_body(ntiles - 1, std::true_type{});
   }
 
+  // ---- drain: softmax of the very last sub-tile
+#pragma unroll
+  for (int m = 0; m < MS; ++m) soft_step(accB0, accB1, m);
+  soft_end(ntiles - 1, 1);
+
   if constexpr (PASS == 2) {
-    reduce_cols((ntiles - 1) & 1, kstart + (ntiles - 1) * kTileKeys);
+    lds_barrier();
+    reduce_cols(ntiles - 2);
+    reduce_cols(ntiles - 1);
   } else {
     // merge the two half-wave views of each row, then one (max*c, sum) pair per row and chunk
     float* st = a.stats + (((int64_t)lz * a.total_chunks + chunk_base + local) * a.rpad) * 2;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-      const float m_o = __shfl_xor(m_run[rb], 32);
-      const float l_o = __shfl_xor(l_run[rb], 32);
-      const float M = fmaxf(m_run[rb], m_o);
-      const float L = l_run[rb] * __builtin_amdgcn_exp2f((m_run[rb] - M) * c) +
-                      l_o * __builtin_amdgcn_exp2f((m_o - M) * c);
+      const float m_r = rb == 0 ? m_run0 : m_run1, l_r = rb == 0 ? l_run0 : l_run1;
+      const float m_o = __shfl_xor(m_r, 32);
+      const float l_o = __shfl_xor(l_r, 32);
+      const float M = fmaxf(m_r, m_o);
+      const float L = l_r * __builtin_amdgcn_exp2f((m_r - M) * c) + l_o * __builtin_amdgcn_exp2f((m_o - M) * c);
       const int row = row0 + rb * 32 + l32;
       if (lane < 32) {
         st[row * 2 + 0] = M * c;
@@ -246,6 +365,8 @@ __global__ __launch_bounds__(NW * 64) void score_pass_kernel(ScoreArgs a) {
       }
     }
   }
+#undef CODECOMP_GLOAD
+#undef CODECOMP_SSTORE
 }
 
 // One thread per (layer*head, request, row): log2-sum-exp over that request's chunks.
