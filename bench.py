@@ -66,6 +66,9 @@ def main() -> int:
     ap.add_argument("--cpu-layers", type=int, default=12, help="layers the CPU oracle is timed and compared on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (experiments only)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain device copy of 1 GiB (reads 1 GiB, writes 1 GiB): the reference "
+                         "dispatch for scaling FETCH_SIZE / WRITE_SIZE counter readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -78,6 +81,15 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU substitute", file=sys.stderr)
         return 3
+    if args.calibrate_copy:
+        src = torch.full((1 << 30,), 7, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": 1 << 30, "calibrate_copy_bytes_written": 1 << 30, "copies": 3}))
+        return 0
     w = wl.CONFIGS[args.workload]()
     if args.layers > 0:
         w = wl.scaled(w, name=f"{w.name}_L{args.layers}", n_layers=args.layers)

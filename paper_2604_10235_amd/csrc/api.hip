@@ -15,7 +15,7 @@ static int chunk_keys_setting() {
   // experiments (multiple of the LDS tile, at least one tile).
   static int cached = 0;
   if (cached == 0) {
-    int v = 1024;
+    int v = 2048;
     if (const char* e = getenv("CODECOMP_CHUNK_KEYS")) {
       int x = atoi(e);
       if (x >= kTileKeys && x % kTileKeys == 0 && x <= (1 << 20)) v = x;
@@ -89,6 +89,7 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   pl->o_sh = p->out_stride_head ? p->out_stride_head : (int64_t)pl->TB * d;
   pl->o_sl = p->out_stride_layer ? p->out_stride_layer : (int64_t)pl->Hkv * pl->TB * d;
   if (pl->q_st < d || pl->kv_st < d || pl->o_st < d) return CODECOMP_EINVAL_SHAPE;
+  if (pl->kv_st > (1 << 20)) return CODECOMP_EINVAL_SHAPE;   // tile staging keeps 32-bit byte offsets inside a tile
   pl->cu_seqlens_dev = p->cu_seqlens_dev;
   pl->cu_budgets_dev = p->cu_budgets_dev;
 

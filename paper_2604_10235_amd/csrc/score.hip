@@ -123,12 +123,29 @@ __global__ __launch_bounds__(NW * 64) void score_pass_kernel(ScoreArgs a) {
   // last key (always in bounds); such columns are masked (pass 1) or never stored (pass 2).
   const uint16_t* kb = a.k + (int64_t)layer * a.kv_sl + (int64_t)head * a.kv_sh + (int64_t)tok0 * a.kv_st;
   u32x4 stage[LD];
+  uint32_t soff[LD];                             // byte offset of this thread's i-th piece inside a tile
+#pragma unroll
+  for (int i = 0; i < LD; ++i) {
+    const int cidx = tid + i * NT;
+    const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;
+    soff[i] = (uint32_t)(row * (int)a.kv_st + col * 8) * 2u;
+  }
+  // fast path: every staged row (slack rows included) lies inside the chunk -> uniform base + lane offset
 #define CODECOMP_GLOAD(KEY0)                                                                        \
-  _Pragma("unroll") for (int i = 0; i < LD; ++i) {                                                  \
-    const int cidx = tid + i * NT;                                                                  \
-    const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;                               \
-    const int key = min((KEY0) + row, kend - 1);                                                    \
-    stage[i] = *reinterpret_cast<const u32x4*>(kb + (int64_t)key * a.kv_st + col * 8);              \
+  {                                                                                                 \
+    const int key0_ = (KEY0);                                                                       \
+    if (key0_ + LDS_ROWS <= kend) {                                                                 \
+      const char* tb_ = reinterpret_cast<const char*>(kb + (int64_t)key0_ * a.kv_st);               \
+      _Pragma("unroll") for (int i = 0; i < LD; ++i)                                                \
+        stage[i] = *reinterpret_cast<const u32x4*>(tb_ + soff[i]);                                  \
+    } else {                                                                                        \
+      _Pragma("unroll") for (int i = 0; i < LD; ++i) {                                              \
+        const int cidx = tid + i * NT;                                                              \
+        const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;                           \
+        const int key = min(key0_ + row, kend - 1);                                                 \
+        stage[i] = *reinterpret_cast<const u32x4*>(kb + (int64_t)key * a.kv_st + col * 8);          \
+      }                                                                                             \
+    }                                                                                               \
   }
 #define CODECOMP_SSTORE(BUF)                                                                        \
   _Pragma("unroll") for (int i = 0; i < LD; ++i) {                                                  \
