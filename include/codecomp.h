@@ -52,7 +52,7 @@ enum {
   CODECOMP_EINVAL_SHAPE = -2,     /* n_layers < 1, n_seqs < 1, a negative stride, G*W too large   */
   CODECOMP_EINVAL_WINDOW = -3,    /* W < 1 or W > N_r for some request                            */
   CODECOMP_EINVAL_BUDGET = -4,    /* B_r < W or B_r > N_r for some request                        */
-  CODECOMP_EINVAL_POOL = -5,      /* pool_kernel even or < 1                                      */
+  CODECOMP_EINVAL_POOL = -5,      /* pool_kernel even, < 1 or > 1025                              */
   CODECOMP_EINVAL_HEADS = -6,     /* n_kv_heads < 1 or n_q_heads not a multiple of n_kv_heads     */
   CODECOMP_EINVAL_HEADDIM = -7,   /* head_dim not in {64, 128}                                    */
   CODECOMP_EINVAL_SEQLENS = -8,   /* cu_seqlens / cu_budgets not starting at 0 or not increasing  */
@@ -66,7 +66,7 @@ typedef struct codecomp_params {
   int32_t n_kv_heads;
   int32_t head_dim;            /* d: 64 or 128                                                    */
   int32_t window;              /* W: the last W tokens of a request are the observation queries   */
-  int32_t pool_kernel;         /* k: odd, >= 1 (1 = no pooling)                                   */
+  int32_t pool_kernel;         /* k: odd, 1 <= k <= 1025 (1 = no pooling)                         */
   float prior_weight;          /* lambda >= 0                                                     */
   float softmax_scale;         /* 0 selects 1/sqrt(head_dim)                                      */
   int32_t n_seqs;              /* number of packed requests; 1 = dense                            */

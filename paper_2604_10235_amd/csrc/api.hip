@@ -31,7 +31,7 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   if ((int64_t)p->n_layers * p->n_kv_heads > 65535) return CODECOMP_EINVAL_SHAPE;   // one grid axis
   if (p->n_kv_heads < 1 || p->n_q_heads < 1 || p->n_q_heads % p->n_kv_heads != 0) return CODECOMP_EINVAL_HEADS;
   if (p->head_dim != 64 && p->head_dim != 128) return CODECOMP_EINVAL_HEADDIM;
-  if (p->pool_kernel < 1 || p->pool_kernel % 2 == 0) return CODECOMP_EINVAL_POOL;
+  if (p->pool_kernel < 1 || p->pool_kernel % 2 == 0 || p->pool_kernel > 1025) return CODECOMP_EINVAL_POOL;
   if (!(p->prior_weight >= 0.0f) || !isfinite(p->prior_weight)) return CODECOMP_EINVAL_PRIOR;
   if (!(p->softmax_scale >= 0.0f) || !isfinite(p->softmax_scale)) return CODECOMP_EINVAL_PRIOR;
   if (!p->cu_seqlens_host || !p->cu_seqlens_dev || !p->cu_budgets_host || !p->cu_budgets_dev)

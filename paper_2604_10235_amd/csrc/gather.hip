@@ -18,8 +18,30 @@ struct GatherArgs {
   int64_t kv_sl, kv_sh, kv_st, o_sl, o_sh, o_st;
 };
 
+#ifndef CODECOMP_GATHER_ROWS
+#define CODECOMP_GATHER_ROWS 2
+#endif
+#ifndef CODECOMP_GATHER_NT
+#define CODECOMP_GATHER_NT 0
+#endif
 constexpr int kGatherThreads = 256;
-constexpr int kGatherRowsPerThread = 4;
+constexpr int kGatherRowsPerThread = CODECOMP_GATHER_ROWS;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ u32x4 ld16(const uint16_t* p) {
+#if CODECOMP_GATHER_NT
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+#else
+  return *reinterpret_cast<const u32x4*>(p);
+#endif
+}
+__device__ __forceinline__ void st16(uint16_t* p, u32x4 v) {
+#if CODECOMP_GATHER_NT
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
+#else
+  *reinterpret_cast<u32x4*>(p) = v;
+#endif
+}
 
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
   const int pieces = 1 << a.pieces_log2;
@@ -35,7 +57,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
   uint16_t* vo = a.v_out + layer * a.o_sl + head * a.o_sh;
   const int slot0 = blockIdx.x * rows_per_pass * kGatherRowsPerThread + rsub;
 
-  uint4 kv[kGatherRowsPerThread], vv[kGatherRowsPerThread];
+  u32x4 kv[kGatherRowsPerThread], vv[kGatherRowsPerThread];
 #pragma unroll
   for (int i = 0; i < kGatherRowsPerThread; ++i) {
     const int slot = slot0 + i * rows_per_pass;
@@ -48,16 +70,16 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
       // indices are clamped into the request so that a corrupt idx can never read out of bounds
       const int s0 = a.cu_seqlens[lo], n = a.cu_seqlens[lo + 1] - s0;
       const int64_t tok = (int64_t)s0 + min(max(idx[slot], 0), n - 1);
-      kv[i] = *reinterpret_cast<const uint4*>(kb + tok * a.kv_st + piece * 8);
-      vv[i] = *reinterpret_cast<const uint4*>(vb + tok * a.kv_st + piece * 8);
+      kv[i] = ld16(kb + tok * a.kv_st + piece * 8);
+      vv[i] = ld16(vb + tok * a.kv_st + piece * 8);
     }
   }
 #pragma unroll
   for (int i = 0; i < kGatherRowsPerThread; ++i) {
     const int slot = slot0 + i * rows_per_pass;
     if (slot < a.TB) {
-      *reinterpret_cast<uint4*>(ko + (int64_t)slot * a.o_st + piece * 8) = kv[i];
-      *reinterpret_cast<uint4*>(vo + (int64_t)slot * a.o_st + piece * 8) = vv[i];
+      st16(ko + (int64_t)slot * a.o_st + piece * 8, kv[i]);
+      st16(vo + (int64_t)slot * a.o_st + piece * 8, vv[i]);
     }
   }
 }

@@ -414,25 +414,40 @@ struct FinishArgs {
   float lambda, inv_pool;
 };
 
+constexpr int kFinishTile = 1024;     // tokens per workgroup of the finish kernel
+constexpr int kFinishHalo = 512;      // largest supported (pool_kernel - 1) / 2
+
 // scores[lz][j] = (1/k) * sum_{|delta| <= (k-1)/2, inside the request} u[lz][j+delta] + lambda * prior[j]
+// One workgroup stages 1024 tokens of u (+ halo, row splits added) in LDS; every output is a direct sum.
 __global__ __launch_bounds__(256) void score_finish_kernel(FinishArgs a) {
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  __shared__ float tile[kFinishTile + 2 * kFinishHalo];
+  const int tid = threadIdx.x;
   const int lz = blockIdx.y;
-  if (j >= a.T) return;
-  int lo = 0, hi = a.n_seqs;            // request containing token j: cu[lo] <= j < cu[lo+1]
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (a.cu_seqlens[mid] <= j) lo = mid; else hi = mid;
-  }
-  const int s0 = a.cu_seqlens[lo], s1 = a.cu_seqlens[lo + 1];
+  const int base = blockIdx.x * kFinishTile;
   const int half = (a.pool - 1) >> 1;
-  const int b0 = max(s0, j - half), b1 = min(s1 - 1, j + half);
-  float sum = 0.f;
-  for (int sp = 0; sp < a.row_splits; ++sp) {
-    const float* u = a.uraw + ((int64_t)sp * a.LH + lz) * a.T;
-    for (int x = b0; x <= b1; ++x) sum += u[x];
+  for (int i = tid; i < kFinishTile + 2 * half; i += 256) {
+    const int x = base - half + i;
+    float val = 0.f;
+    if (x >= 0 && x < a.T)
+      for (int sp = 0; sp < a.row_splits; ++sp) val += a.uraw[((int64_t)sp * a.LH + lz) * a.T + x];
+    tile[i] = val;
   }
-  a.scores[(int64_t)lz * a.T + j] = __builtin_fmaf(a.lambda, a.prior[j], sum * a.inv_pool);
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < kFinishTile / 256; ++e) {
+    const int j = base + e * 256 + tid;
+    if (j >= a.T) continue;
+    int lo = 0, hi = a.n_seqs;          // request containing token j: cu[lo] <= j < cu[lo+1]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (a.cu_seqlens[mid] <= j) lo = mid; else hi = mid;
+    }
+    const int s0 = a.cu_seqlens[lo], s1 = a.cu_seqlens[lo + 1];
+    const int b0 = max(s0, j - half), b1 = min(s1 - 1, j + half);
+    float sum = 0.f;
+    for (int x = b0; x <= b1; ++x) sum += tile[x - base + half];
+    a.scores[(int64_t)lz * a.T + j] = __builtin_fmaf(a.lambda, a.prior[j], sum * a.inv_pool);
+  }
 }
 
 template <int D, int NW>
@@ -495,7 +510,7 @@ int launch_score(const Plan& pl, const void* q, const void* k, const float* prio
   f.uraw = a.uraw; f.prior = prior; f.cu_seqlens = pl.cu_seqlens_dev; f.scores = scores;
   f.n_seqs = pl.n_seqs; f.T = pl.T; f.LH = pl.L * pl.Hkv; f.row_splits = pl.row_splits; f.pool = pl.pool;
   f.lambda = pl.lambda; f.inv_pool = 1.0f / (float)pl.pool;
-  score_finish_kernel<<<dim3((pl.T + 255) / 256, pl.L * pl.Hkv), dim3(256), 0, stream>>>(f);
+  score_finish_kernel<<<dim3((pl.T + kFinishTile - 1) / kFinishTile, pl.L * pl.Hkv), dim3(256), 0, stream>>>(f);
   if (hipError_t e = hipGetLastError()) return (int)e;
   return 0;
 }

@@ -3,7 +3,7 @@
 // ascending ("retain the top-ranked context tokens ... up to the remaining chunk budget").
 //
 // One workgroup owns one problem.  An MSB-first radix select over order-preserving integer
-// images of the float scores (4 passes of 8 bits, 256-bin LDS histogram) finds the score of
+// images of the float scores (digits of 11, 11 and 10 bits, LDS histogram) finds the score of
 // the last admitted token and how many tokens tied at that score are admitted; one ordered
 // pass (workgroup prefix sums of "greater" and "equal" flags) then writes the indices already
 // sorted.  The score row (<= 512 KB) stays in L2 between passes.
@@ -29,7 +29,7 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   constexpr int NT = kSelectThreads;
   constexpr int NWV = NT / 64;
-  __shared__ unsigned int hist[256];
+  __shared__ unsigned int hist[2048];
   __shared__ unsigned int sh_prefix, sh_need;
   __shared__ int wave_gt[NWV], wave_eq[NWV];
   __shared__ int tile_gt, tile_eq;
@@ -55,38 +55,69 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
     return;
   }
 
-  // ---- radix select: key of the need-th largest candidate
+  // ---- radix select: key of the need-th largest candidate (digits of 11, 11, 10 bits, MSB first)
   uint32_t prefix = 0;                   // high bits fixed so far
   uint32_t remaining = (uint32_t)need;   // rank still to be located inside the current bucket
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    for (int b = tid; b < 256; b += NT) hist[b] = 0;
+  const int npad = (npre + NT - 1) / NT * NT;   // uniform trip counts: every lane takes part in the ballots
+#pragma unroll
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
+    const int nbins = pass == 2 ? 1024 : 2048;
+    for (int b = tid; b < nbins; b += NT) hist[b] = 0;
     __syncthreads();
-    const uint32_t himask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
-    for (int j = tid; j < npre; j += NT) {
-      const uint32_t key = order_key(sc[j]);
-      if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (pass == 1 ? 21 : 10));
+    constexpr int UNR = 8;                // loads in flight per thread: the pass is latency bound otherwise
+    for (int j0 = tid; j0 < npad; j0 += NT * UNR) {
+      uint32_t keys[UNR];
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const int j = j0 + u * NT;
+        keys[u] = j < npre ? order_key(sc[j]) : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const int j = j0 + u * NT;
+        const uint32_t key = keys[u];
+        const bool match = j < npre && (key & himask) == prefix;
+        const uint32_t bin = (key >> shift) & (uint32_t)(nbins - 1);
+        // score distributions are concentrated: lanes that share a bin are counted with one atomic
+        // (two rounds of leader election), whatever is left falls back to one atomic per lane
+        unsigned long long pend = __ballot(match);
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+          if (pend != 0) {
+            const int leader = __ffsll(pend) - 1;
+            const uint32_t lb = __shfl(bin, leader);
+            const unsigned long long same = __ballot(match && bin == lb) & pend;
+            if (lane == leader) atomicAdd(&hist[lb], (unsigned int)__popcll(same));
+            pend &= ~same;
+          }
+        }
+        if ((pend >> lane) & 1ull) atomicAdd(&hist[bin], 1u);
+      }
     }
     __syncthreads();
     if (wave == 0) {
-      // lane owns bins 4*lane .. 4*lane+3; walk from the top bin down until `remaining` is covered
-      unsigned int c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
-      unsigned int mine = c0 + c1 + c2 + c3;
-      unsigned int above = 0;            // count in bins owned by higher lanes
+      // lane owns bins [lane*per, lane*per+per); walk from the top bin down until `remaining` is covered
+      const int per = nbins / 64;
+      unsigned int mine = 0;
+      for (int i = 0; i < per; ++i) mine += hist[lane * per + i];
       unsigned int run = mine;           // inclusive suffix sum over lanes
 #pragma unroll
       for (int off = 1; off < 64; off <<= 1) {
         const unsigned int o = __shfl_down(run, off);
         if (lane + off < 64) run += o;
       }
-      above = run - mine;
+      const unsigned int above = run - mine;   // count in bins owned by higher lanes
       if (above < remaining && remaining <= above + mine) {   // exactly one lane
         unsigned int acc = above;
-        int bin;
-        if (acc + c3 >= remaining) bin = 3;
-        else { acc += c3; if (acc + c2 >= remaining) bin = 2;
-        else { acc += c2; if (acc + c1 >= remaining) bin = 1;
-        else { acc += c1; bin = 0; } } }
-        sh_prefix = prefix | ((uint32_t)(4 * lane + bin) << shift);
+        int bin = per - 1;
+        for (; bin > 0; --bin) {
+          const unsigned int cnt = hist[lane * per + bin];
+          if (acc + cnt >= remaining) break;
+          acc += cnt;
+        }
+        sh_prefix = prefix | ((uint32_t)(lane * per + bin) << shift);
         sh_need = remaining - acc;       // rank inside the chosen bin
       }
     }
