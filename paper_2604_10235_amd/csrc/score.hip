@@ -67,7 +67,7 @@ __device__ __forceinline__ f32x16 mma_step(u32x4 qfrag, u32x4 kfrag, f32x16 acc)
 }
 
 template <int D, int NW, int PASS>
-__global__ __launch_bounds__(NW * 64) void score_pass_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(ScoreArgs a) {
   constexpr int NT = NW * 64;
   constexpr int KS = D / 16;                   // MFMA k-steps per logit
   constexpr int ROWB = D * 2 + 16;             // LDS bytes per key row (+16: spreads rows over banks)
