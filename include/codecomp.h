@@ -57,7 +57,8 @@ enum {
   CODECOMP_EINVAL_HEADDIM = -7,   /* head_dim not in {64, 128}                                    */
   CODECOMP_EINVAL_SEQLENS = -8,   /* cu_seqlens / cu_budgets not starting at 0 or not increasing  */
   CODECOMP_EINVAL_WORKSPACE = -9, /* workspace NULL, misaligned (256 B) or too small              */
-  CODECOMP_EINVAL_PRIOR = -10     /* prior_weight negative or not finite; softmax_scale < 0       */
+  CODECOMP_EINVAL_PRIOR = -10,    /* prior_weight negative or not finite; softmax_scale < 0       */
+  CODECOMP_EINVAL_MODE = -11      /* select_mode unknown, wrong for the call, or bad span budget  */
 };
 
 typedef struct codecomp_params {
@@ -70,7 +71,7 @@ typedef struct codecomp_params {
   float prior_weight;          /* lambda >= 0                                                     */
   float softmax_scale;         /* 0 selects 1/sqrt(head_dim)                                      */
   int32_t n_seqs;              /* number of packed requests; 1 = dense                            */
-  int32_t reserved0;           /* must be 0                                                       */
+  int32_t select_mode;         /* CODECOMP_SELECT_ADDITIVE (0) or CODECOMP_SELECT_TWO_STAGE (1)  */
   const int32_t* cu_seqlens_host; /* [n_seqs+1] HOST copy: sizes the launches and is validated    */
   const int32_t* cu_seqlens_dev;  /* [n_seqs+1] DEVICE copy of the same values                    */
   const int32_t* cu_budgets_host; /* [n_seqs+1] HOST                                              */
@@ -79,7 +80,21 @@ typedef struct codecomp_params {
   int64_t q_stride_layer, q_stride_seq, q_stride_head, q_stride_tok;
   int64_t kv_stride_layer, kv_stride_head, kv_stride_tok;      /* shared by k and v              */
   int64_t out_stride_layer, out_stride_head, out_stride_tok;   /* shared by k_out and v_out      */
+  /* two-stage selection only (ignored otherwise): span budget = min(Bp, max(span_budget_min,
+   * floor(span_budget_ratio * Bp))) with Bp = B_r - W; the paper uses a ratio of 0.5 */
+  float span_budget_ratio;     /* rho_span in [0, 1]                                              */
+  int32_t span_budget_min;     /* B_min >= 0                                                      */
 } codecomp_params;
+
+/* How the structural prior enters the selection.
+ * ADDITIVE : scores = pooled attention + lambda * prior, one top-(B - W) over them.
+ * TWO_STAGE: the order stated in sections "Span-Level Structural Protection" / "Attention-based KV Cache
+ *            Compression": first up to span-budget prefix tokens with prior > 0 are kept, largest prior
+ *            first (equal priors: first in sequence), then pooled attention fills the remaining B - W - |P|
+ *            slots among the other prefix tokens.  In this mode codecomp_score leaves the prior out
+ *            (scores = pooled attention, prior_weight is ignored) and codecomp_compress selects with
+ *            codecomp_select_two_stage. */
+enum { CODECOMP_SELECT_ADDITIVE = 0, CODECOMP_SELECT_TWO_STAGE = 1 };
 
 /* Host-only: bytes of device workspace the calls below need for these parameters (the largest
  * of score / select / compress).  Returns 0 when the parameters are invalid. Never touches a GPU. */
@@ -119,6 +134,11 @@ int codecomp_score_stages(const void* q_obs, const void* k, const float* prior, 
 int codecomp_select(const float* scores, const codecomp_params* params, int32_t* idx,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The two-stage rule (see CODECOMP_SELECT_TWO_STAGE) on `scores` = pooled attention and the per-token
+ * `prior`; params->select_mode must be CODECOMP_SELECT_TWO_STAGE.  Output as codecomp_select. */
+int codecomp_select_two_stage(const float* scores, const float* prior, const codecomp_params* params, int32_t* idx,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* k_out[l][h][cu_budgets[r] + i][:] = k[l][h][cu_seqlens[r] + idx[l][h][cu_budgets[r] + i]][:],
  * same for v: a bit copy of the retained rows (the compact per-layer cache).  idx values must lie
  * in [0, N_r). */
@@ -129,6 +149,26 @@ int codecomp_gather(const void* k, const void* v, const int32_t* idx, const code
 int codecomp_compress(const void* q_obs, const void* k, const void* v, const float* prior,
                       const codecomp_params* params, float* scores, int32_t* idx, void* k_out, void* v_out,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Str. Score of section "Experiment": retained[l][h][r] = |{kept tokens j of request r : prior[j] > 0}| /
+ * |{tokens j of request r : prior[j] > 0}| (NaN when the request has no such token).  `retained` is a
+ * device f32 [n_layers][n_kv_heads][n_seqs]; idx as written by codecomp_select. */
+int codecomp_structure_score(const int32_t* idx, const float* prior, const codecomp_params* params, float* retained,
+                             void* hip_stream);
+
+/* Host-only arithmetic of sections "Structural Feature Extraction" and "Structure-Aware Budget Allocation"
+ * (all pointers are HOST pointers; nothing touches a GPU).
+ *   sigma_i = sum_k w_k * min(1, log(1 + f_ik) / log(1 + tau_k))          features [n_chunks][n_features] >= 0
+ *   s_i = 0.5 if all sigma are equal, else (sigma_i - sigma_min) / max(eps, sigma_max - sigma_min)
+ *   m_i = m_min + (m_max - m_min) * clip(s_i, 0, 1)
+ *   B_i = floor(len_i * min(r_max, ratio * m_i)), then clamped into [window, len_i] because the hot path
+ *         always keeps the observation window (pass window = 0 for the paper's bare formula).
+ * The feature scales tau_k, weights w_k, eps, r_max are not given in the paper: they are arguments. */
+int codecomp_chunk_structure_scores(const double* features_host, const double* tau_host, const double* weights_host,
+                                    int32_t n_chunks, int32_t n_features, double* sigma_host);
+int codecomp_chunk_budgets(const double* sigma_host, const int32_t* chunk_len_host, int32_t n_chunks, double ratio,
+                           double m_min, double m_max, double r_max, double eps, int32_t window,
+                           int32_t* budgets_host);
 
 /* Host-only: static description of a status code returned by the calls above. */
 const char* codecomp_status_string(int status);

@@ -191,3 +191,82 @@ def compress_packed(q_bits, k_bits, v_bits, prior, cu_seqlens, cu_budgets, *, wi
     idx = select_packed(sc, cu_seqlens, cu_budgets, window)
     k_out, v_out = gather_packed(k_bits, v_bits, idx, cu_seqlens, cu_budgets)
     return sc, idx, k_out, v_out
+
+
+# ----------------------------------------------------------------------------------------
+# structure-aware budgets (host-side arithmetic of section "Structure-Aware Budget Allocation")
+# ----------------------------------------------------------------------------------------
+
+def log_norm(x, tau):
+    """Norm(x; tau) = min(1, log(1 + x) / log(1 + tau))  (section "Structural Feature Extraction")."""
+    return np.minimum(1.0, np.log1p(np.asarray(x, dtype=np.float64)) / np.log1p(np.asarray(tau, dtype=np.float64)))
+
+
+def chunk_structure_score(features, tau, weights):
+    """sigma_i = sum_k w_k * Norm(f_ik; tau_k); features [n_chunks, K]."""
+    return (log_norm(features, tau) * np.asarray(weights, dtype=np.float64)).sum(axis=1)
+
+
+def chunk_budgets(sigma, chunk_len, *, ratio, m_min, m_max, r_max, eps):
+    """B_i = floor(|C_i| * min(r_max, r * m_i)) with
+    s_i = 0.5 if all sigma are equal else (sigma_i - sigma_min) / max(eps, sigma_max - sigma_min),
+    m_i = m_min + (m_max - m_min) * clip(s_i, 0, 1)."""
+    sigma = np.asarray(sigma, dtype=np.float64)
+    lo, hi = sigma.min(), sigma.max()
+    if hi == lo:
+        s = np.full_like(sigma, 0.5)
+    else:
+        s = (sigma - lo) / max(eps, hi - lo)
+    m = m_min + (m_max - m_min) * np.clip(s, 0.0, 1.0)
+    return np.floor(np.asarray(chunk_len, dtype=np.float64) * np.minimum(r_max, ratio * m)).astype(np.int64)
+
+
+# ----------------------------------------------------------------------------------------
+# structure score: fraction of structurally critical tokens that survive compression
+# ----------------------------------------------------------------------------------------
+
+def structure_score(idx, prior, n):
+    """Per head: |{kept j : p[j] > 0}| / |{j < n : p[j] > 0}| (section "Experiment", Str. Score; the
+    structurally critical tokens are those the prior marks).  idx [H, B]; NaN when nothing is marked."""
+    flagged = np.asarray(prior[:n]) > 0
+    total = int(flagged.sum())
+    out = np.full(idx.shape[0], np.nan)
+    if total:
+        for h in range(idx.shape[0]):
+            out[h] = flagged[idx[h]].sum() / total
+    return out
+
+
+# ----------------------------------------------------------------------------------------
+# the paper's literal order: structure first, attention fills the rest
+# ----------------------------------------------------------------------------------------
+
+def span_budget(prefix_budget: int, ratio: float, minimum: int) -> int:
+    """B_span = min(B, max(B_min, floor(rho_span * B)))  (section "Span-Level Structural Protection")."""
+    return int(min(prefix_budget, max(minimum, np.floor(ratio * prefix_budget))))
+
+
+def select_two_stage(pooled: np.ndarray, prior: np.ndarray, window: int, budget: int, *, span_ratio: float,
+                     span_min: int) -> np.ndarray:
+    """Kept indices per head, int64 [H, budget], ascending.
+
+    Token-level form of the two-stage rule on a dense prior: the last `window` tokens are always
+    kept; of the Bp = budget - window prefix slots, stage 1 gives up to B_span to tokens the prior
+    marks (p > 0), largest p first, equal p first in sequence; stage 2 gives the remaining slots to
+    the other prefix tokens by pooled attention mass (descending, equal mass first in sequence)."""
+    h, n = pooled.shape
+    assert 1 <= window <= n and window <= budget <= n
+    npre, bp = n - window, budget - window
+    p = np.asarray(prior[:npre], dtype=np.float64)
+    marked = np.flatnonzero(p > 0)
+    by_prior = marked[np.argsort(-p[marked], kind="stable")]
+    protected = by_prior[: min(span_budget(bp, span_ratio, span_min), len(marked))]
+    is_protected = np.zeros(npre, dtype=bool)
+    is_protected[protected] = True
+    others = np.flatnonzero(~is_protected)
+    tail = np.arange(npre, n, dtype=np.int64)
+    out = np.empty((h, budget), dtype=np.int64)
+    for i in range(h):
+        fill = others[np.argsort(-pooled[i, others], kind="stable")][: bp - len(protected)]
+        out[i] = np.concatenate([np.sort(np.concatenate([protected, fill])), tail])
+    return out

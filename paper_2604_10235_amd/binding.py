@@ -21,7 +21,7 @@ STATUS = {
     0: "CODECOMP_OK", -1: "CODECOMP_EINVAL_NULL", -2: "CODECOMP_EINVAL_SHAPE", -3: "CODECOMP_EINVAL_WINDOW",
     -4: "CODECOMP_EINVAL_BUDGET", -5: "CODECOMP_EINVAL_POOL", -6: "CODECOMP_EINVAL_HEADS",
     -7: "CODECOMP_EINVAL_HEADDIM", -8: "CODECOMP_EINVAL_SEQLENS", -9: "CODECOMP_EINVAL_WORKSPACE",
-    -10: "CODECOMP_EINVAL_PRIOR",
+    -10: "CODECOMP_EINVAL_PRIOR", -11: "CODECOMP_EINVAL_MODE",
 }
 
 
@@ -29,13 +29,14 @@ class codecomp_params(C.Structure):
     _fields_ = [
         ("n_layers", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("window", C.c_int32), ("pool_kernel", C.c_int32), ("prior_weight", C.c_float), ("softmax_scale", C.c_float),
-        ("n_seqs", C.c_int32), ("reserved0", C.c_int32),
+        ("n_seqs", C.c_int32), ("select_mode", C.c_int32),
         ("cu_seqlens_host", C.c_void_p), ("cu_seqlens_dev", C.c_void_p),
         ("cu_budgets_host", C.c_void_p), ("cu_budgets_dev", C.c_void_p),
         ("q_stride_layer", C.c_int64), ("q_stride_seq", C.c_int64), ("q_stride_head", C.c_int64),
         ("q_stride_tok", C.c_int64),
         ("kv_stride_layer", C.c_int64), ("kv_stride_head", C.c_int64), ("kv_stride_tok", C.c_int64),
         ("out_stride_layer", C.c_int64), ("out_stride_head", C.c_int64), ("out_stride_tok", C.c_int64),
+        ("span_budget_ratio", C.c_float), ("span_budget_min", C.c_int32),
     ]
 
 
@@ -69,11 +70,21 @@ def lib() -> C.CDLL:
                                             C.c_uint, C.c_void_p]
         l.codecomp_select.restype = C.c_int
         l.codecomp_select.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        l.codecomp_select_two_stage.restype = C.c_int
+        l.codecomp_select_two_stage.argtypes = [C.c_void_p, C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         l.codecomp_gather.restype = C.c_int
         l.codecomp_gather.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_void_p]
         l.codecomp_compress.restype = C.c_int
         l.codecomp_compress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, P, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        l.codecomp_structure_score.restype = C.c_int
+        l.codecomp_structure_score.argtypes = [C.c_void_p, C.c_void_p, P, C.c_void_p, C.c_void_p]
+        DP, IP = C.POINTER(C.c_double), C.POINTER(C.c_int32)
+        l.codecomp_chunk_structure_scores.restype = C.c_int
+        l.codecomp_chunk_structure_scores.argtypes = [DP, DP, DP, C.c_int32, C.c_int32, DP]
+        l.codecomp_chunk_budgets.restype = C.c_int
+        l.codecomp_chunk_budgets.argtypes = [DP, IP, C.c_int32, C.c_double, C.c_double, C.c_double, C.c_double,
+                                             C.c_double, C.c_int32, IP]
         l.codecomp_status_string.restype = C.c_char_p
         l.codecomp_status_string.argtypes = [C.c_int]
         l.codecomp_version.restype = C.c_int
@@ -105,8 +116,8 @@ def make_params(*, n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int
     p.cu_budgets_host = cbl.ctypes.data
     p.cu_seqlens_dev = cu_seqlens_dev
     p.cu_budgets_dev = cu_budgets_dev
-    for name, val in strides.items():
-        setattr(p, name, int(val))
+    for name, val in strides.items():      # strides, select_mode, span_budget_*
+        setattr(p, name, val)
     p._keep = (csl, cbl)
     return p
 
@@ -152,6 +163,12 @@ def codecomp_select(scores, params, idx, workspace) -> None:
                                  workspace.numel() * workspace.element_size(), _stream()), "codecomp_select")
 
 
+def codecomp_select_two_stage(scores, prior, params, idx, workspace) -> None:
+    _check(lib().codecomp_select_two_stage(_ptr(scores), _ptr(prior), C.byref(params), _ptr(idx), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream()),
+           "codecomp_select_two_stage")
+
+
 def codecomp_gather(k, v, idx, params, k_out, v_out) -> None:
     _check(lib().codecomp_gather(_ptr(k), _ptr(v), _ptr(idx), C.byref(params), _ptr(k_out), _ptr(v_out), _stream()),
            "codecomp_gather")
@@ -163,12 +180,42 @@ def codecomp_compress(q_obs, k, v, prior, params, scores, idx, k_out, v_out, wor
                                    workspace.numel() * workspace.element_size(), _stream()), "codecomp_compress")
 
 
+def codecomp_structure_score(idx, prior, params, retained) -> None:
+    _check(lib().codecomp_structure_score(_ptr(idx), _ptr(prior), C.byref(params), _ptr(retained), _stream()),
+           "codecomp_structure_score")
+
+
+def _dp(a):
+    return a.ctypes.data_as(C.POINTER(C.c_double))
+
+
+def codecomp_chunk_structure_scores(features, tau, weights) -> np.ndarray:
+    f = np.ascontiguousarray(features, dtype=np.float64)
+    t = np.ascontiguousarray(tau, dtype=np.float64)
+    w = np.ascontiguousarray(weights, dtype=np.float64)
+    out = np.empty(f.shape[0], dtype=np.float64)
+    _check(lib().codecomp_chunk_structure_scores(_dp(f), _dp(t), _dp(w), f.shape[0], f.shape[1], _dp(out)),
+           "codecomp_chunk_structure_scores")
+    return out
+
+
+def codecomp_chunk_budgets(sigma, chunk_len, *, ratio, m_min, m_max, r_max, eps, window) -> np.ndarray:
+    s = np.ascontiguousarray(sigma, dtype=np.float64)
+    ln = np.ascontiguousarray(chunk_len, dtype=np.int32)
+    out = np.empty(len(s), dtype=np.int32)
+    ip = C.POINTER(C.c_int32)
+    _check(lib().codecomp_chunk_budgets(_dp(s), ln.ctypes.data_as(ip), len(s), ratio, m_min, m_max, r_max, eps, window,
+                                        out.ctypes.data_as(ip)), "codecomp_chunk_budgets")
+    return out
+
+
 class DeviceProblem:
     """Device buffers of one workload: inputs uploaded from the host arrays of the workload
     generator, outputs and workspace allocated with torch.  Plumbing only."""
 
     def __init__(self, w, q_bits: np.ndarray, k_bits: np.ndarray, v_bits: Optional[np.ndarray], prior: np.ndarray,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", select_mode: int = 0, span_budget_ratio: float = 0.5,
+                 span_budget_min: int = 0):
         import torch
         self.w = w
         dev = torch.device(device)
@@ -187,7 +234,8 @@ class DeviceProblem:
                                   head_dim=w.head_dim, window=w.window, pool_kernel=w.pool_kernel,
                                   prior_weight=w.prior_weight, cu_seqlens_host=w.cu_seqlens(),
                                   cu_budgets_host=w.cu_budgets(), cu_seqlens_dev=_ptr(self.cu_seqlens),
-                                  cu_budgets_dev=_ptr(self.cu_budgets))
+                                  cu_budgets_dev=_ptr(self.cu_budgets), select_mode=select_mode,
+                                  span_budget_ratio=span_budget_ratio, span_budget_min=span_budget_min)
         rc = codecomp_validate(self.params)
         _check(rc, "codecomp_validate")
         T, TB = w.total_tokens, w.total_budget
@@ -204,7 +252,10 @@ class DeviceProblem:
         codecomp_score_stages(self.q, self.k, self.prior, self.params, self.scores, self.workspace, stages)
 
     def select(self):
-        codecomp_select(self.scores, self.params, self.idx, self.workspace)
+        if self.params.select_mode == 1:
+            codecomp_select_two_stage(self.scores, self.prior, self.params, self.idx, self.workspace)
+        else:
+            codecomp_select(self.scores, self.params, self.idx, self.workspace)
 
     def gather(self):
         codecomp_gather(self.k, self.v, self.idx, self.params, self.k_out, self.v_out)

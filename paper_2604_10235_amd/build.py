@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcodecomp.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "gather.hip"]
+SOURCES = ["api.hip", "score.hip", "select.hip", "gather.hip", "structure.hip"]
 # packed fp32 VALU ops are switched off on purpose (device pass only; the host pass ignores it)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"),
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -27,7 +27,11 @@ static int chunk_keys_setting() {
 
 int make_plan(const codecomp_params* p, Plan* pl) {
   if (!p) return CODECOMP_EINVAL_NULL;
-  if (p->n_layers < 1 || p->n_seqs < 1 || p->n_seqs > 65535 || p->reserved0 != 0) return CODECOMP_EINVAL_SHAPE;
+  if (p->n_layers < 1 || p->n_seqs < 1 || p->n_seqs > 65535) return CODECOMP_EINVAL_SHAPE;
+  if (p->select_mode != CODECOMP_SELECT_ADDITIVE && p->select_mode != CODECOMP_SELECT_TWO_STAGE) return CODECOMP_EINVAL_MODE;
+  if (p->select_mode == CODECOMP_SELECT_TWO_STAGE &&
+      (!(p->span_budget_ratio >= 0.0f) || !(p->span_budget_ratio <= 1.0f) || p->span_budget_min < 0))
+    return CODECOMP_EINVAL_MODE;
   if ((int64_t)p->n_layers * p->n_kv_heads > 65535) return CODECOMP_EINVAL_SHAPE;   // one grid axis
   if (p->n_kv_heads < 1 || p->n_q_heads < 1 || p->n_q_heads % p->n_kv_heads != 0) return CODECOMP_EINVAL_HEADS;
   if (p->head_dim != 64 && p->head_dim != 128) return CODECOMP_EINVAL_HEADDIM;
@@ -55,7 +59,10 @@ int make_plan(const codecomp_params* p, Plan* pl) {
 
   pl->L = p->n_layers; pl->Hq = p->n_q_heads; pl->Hkv = p->n_kv_heads; pl->G = pl->Hq / pl->Hkv;
   pl->d = p->head_dim; pl->W = p->window; pl->pool = p->pool_kernel; pl->n_seqs = p->n_seqs;
-  pl->lambda = p->prior_weight;
+  pl->select_mode = p->select_mode;
+  pl->span_ratio = p->span_budget_ratio; pl->span_min = p->span_budget_min;
+  // two-stage selection keeps the prior out of the scores: structure is handled by the selection itself
+  pl->lambda = p->select_mode == CODECOMP_SELECT_TWO_STAGE ? 0.0f : p->prior_weight;
   pl->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
   pl->T = p->cu_seqlens_host[p->n_seqs];
   pl->TB = p->cu_budgets_host[p->n_seqs];
@@ -100,6 +107,8 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   pl->off_stats = off; off = align256(off + LH * pl->total_chunks * rpad * 2 * sizeof(float));
   pl->off_lse = off;   off = align256(off + LH * pl->n_seqs * rpad * sizeof(float));
   pl->off_uraw = off;  off = align256(off + (size_t)pl->row_splits * LH * pl->T * sizeof(float));
+  pl->off_member = off; off = align256(off + (size_t)pl->T);
+  pl->off_member_count = off; off = align256(off + (size_t)pl->n_seqs * sizeof(int32_t));
   pl->ws_bytes = off;
   return CODECOMP_OK;
 }
@@ -155,8 +164,19 @@ int codecomp_select(const float* scores, const codecomp_params* params, int32_t*
   if (!scores || !params || !idx) return CODECOMP_EINVAL_NULL;
   Plan pl;
   if (int rc = make_plan(params, &pl)) return rc;
+  if (pl.select_mode != CODECOMP_SELECT_ADDITIVE) return CODECOMP_EINVAL_MODE;   // the prior is needed: other entry
   if (int rc = check_ws(pl, workspace, workspace_bytes)) return rc;
   return launch_select(pl, scores, idx, (hipStream_t)hip_stream);
+}
+
+int codecomp_select_two_stage(const float* scores, const float* prior, const codecomp_params* params, int32_t* idx,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!scores || !prior || !params || !idx) return CODECOMP_EINVAL_NULL;
+  Plan pl;
+  if (int rc = make_plan(params, &pl)) return rc;
+  if (pl.select_mode != CODECOMP_SELECT_TWO_STAGE) return CODECOMP_EINVAL_MODE;
+  if (int rc = check_ws(pl, workspace, workspace_bytes)) return rc;
+  return launch_select_two_stage(pl, scores, prior, idx, workspace, (hipStream_t)hip_stream);
 }
 
 int codecomp_gather(const void* k, const void* v, const int32_t* idx, const codecomp_params* params,
@@ -179,7 +199,11 @@ int codecomp_compress(const void* q_obs, const void* k, const void* v, const flo
   if (int rc = check_ws(pl, workspace, workspace_bytes)) return rc;
   hipStream_t s = (hipStream_t)hip_stream;
   if (int rc = launch_score(pl, q_obs, k, prior, scores, workspace, s)) return rc;
-  if (int rc = launch_select(pl, scores, idx, s)) return rc;
+  if (pl.select_mode == CODECOMP_SELECT_TWO_STAGE) {
+    if (int rc = launch_select_two_stage(pl, scores, prior, idx, workspace, s)) return rc;
+  } else {
+    if (int rc = launch_select(pl, scores, idx, s)) return rc;
+  }
   return launch_gather(pl, k, v, idx, k_out, v_out, s);
 }
 
@@ -196,6 +220,7 @@ const char* codecomp_status_string(int status) {
     case CODECOMP_EINVAL_SEQLENS: return "cu_seqlens / cu_budgets must start at 0 and increase";
     case CODECOMP_EINVAL_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
     case CODECOMP_EINVAL_PRIOR: return "prior_weight / softmax_scale must be finite and >= 0";
+    case CODECOMP_EINVAL_MODE: return "select_mode unknown or wrong for this call, or span budget out of range";
     default: return status > 0 ? "HIP runtime error (hipError_t value)" : "unknown status";
   }
 }

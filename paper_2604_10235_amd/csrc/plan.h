@@ -16,6 +16,8 @@ constexpr int kSelectThreads = 1024;  // one workgroup per (layer, head, request
 struct Plan {
   int L, Hq, Hkv, G, d, W, pool, n_seqs;
   float lambda, scale;
+  int select_mode;           // CODECOMP_SELECT_*
+  float span_ratio; int span_min;
   int T, TB;                 // total tokens / total output slots over the packed requests
   int max_n;                 // longest request
   int R;                     // G * W softmax rows per (layer, KV head, request)
@@ -30,7 +32,7 @@ struct Plan {
   const int32_t* cu_seqlens_dev;
   const int32_t* cu_budgets_dev;
   // workspace layout (byte offsets, each 256-byte aligned)
-  size_t off_stats, off_lse, off_uraw, ws_bytes;
+  size_t off_stats, off_lse, off_uraw, off_member, off_member_count, ws_bytes;
 };
 
 // Validates `p` and fills `plan`.  Returns 0 or a CODECOMP_E* code.  Host only, no HIP calls.
@@ -39,6 +41,8 @@ int make_plan(const codecomp_params* p, Plan* plan);
 int launch_score(const Plan& pl, const void* q, const void* k, const float* prior, float* scores,
                  void* workspace, hipStream_t stream, unsigned stages = CODECOMP_STAGE_ALL);
 int launch_select(const Plan& pl, const float* scores, int32_t* idx, hipStream_t stream);
+int launch_select_two_stage(const Plan& pl, const float* scores, const float* prior, int32_t* idx, void* workspace,
+                            hipStream_t stream);
 int launch_gather(const Plan& pl, const void* k, const void* v, const int32_t* idx, void* k_out, void* v_out,
                   hipStream_t stream);
 

@@ -29,15 +29,17 @@ def test_every_declared_symbol_is_exported():
     names = declared_functions()
     assert {"codecomp_score", "codecomp_select", "codecomp_gather", "codecomp_compress",
             "codecomp_workspace_bytes", "codecomp_validate", "codecomp_status_string", "codecomp_version",
-            "codecomp_score_stages"} <= set(names)
+            "codecomp_score_stages", "codecomp_select_two_stage", "codecomp_structure_score",
+            "codecomp_chunk_budgets", "codecomp_chunk_structure_scores"} <= set(names)
     lib = b.lib()
     for n in names:
         assert hasattr(lib, n), n
 
 
 def test_struct_layout_matches_header():
-    # 10 x 4-byte fields, 4 pointers, 10 x int64 strides
-    assert C.sizeof(b.codecomp_params) == 40 + 32 + 80
+    # 10 x 4-byte fields, 4 pointers, 10 x int64 strides, span budget (float + int32)
+    assert C.sizeof(b.codecomp_params) == 40 + 32 + 80 + 8
+    assert b.codecomp_params.span_budget_ratio.offset == 152
     assert b.codecomp_params.cu_seqlens_host.offset == 40
     assert b.codecomp_params.q_stride_layer.offset == 72
 
@@ -78,6 +80,10 @@ def test_valid_params_and_workspace_size():
     (dict(cu_seqlens_dev=0), -1),
     (dict(kv_stride_tok=100), -2),                                  # not a multiple of 8 elements
     (dict(kv_stride_tok=64), -2),                                   # rows would overlap
+    (dict(select_mode=2), -11),
+    (dict(select_mode=1, span_budget_ratio=1.5), -11),
+    (dict(select_mode=1, span_budget_ratio=0.5, span_budget_min=-1), -11),
+    (dict(pool_kernel=1027), -5),
 ])
 def test_rejected_parameters(over, code):
     p = good(**over)
@@ -103,6 +109,11 @@ def test_launching_calls_validate_before_touching_a_gpu():
     assert lib.codecomp_score_stages(fake, fake, fake, C.byref(p), fake, fake, 1 << 30, 0, None) == -2
     assert lib.codecomp_score_stages(fake, fake, fake, C.byref(p), fake, fake, 1 << 30, 16, None) == -2
     assert lib.codecomp_compress(fake, fake, None, fake, C.byref(p), fake, fake, fake, fake, fake, 1 << 30, None) == -1
+    # the two selection entry points refuse the other mode
+    assert lib.codecomp_select_two_stage(fake, fake, C.byref(p), fake, fake, 1 << 30, None) == -11
+    p2 = good(select_mode=1, span_budget_ratio=0.5)
+    assert lib.codecomp_select(fake, C.byref(p2), fake, fake, 1 << 30, None) == -11
+    assert lib.codecomp_structure_score(None, fake, C.byref(p), fake, None) == -1
 
 
 def test_binding_raises_with_status_text():
@@ -130,3 +141,25 @@ def test_workload_recipes():
     import torch
     ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(wl.f32_to_bf16_bits(x), ref)
+
+
+def test_host_budget_functions_match_oracle():
+    from oracle import codecomp_oracle as orc
+    g = np.random.default_rng(5)
+    feats = g.integers(0, 60, size=(9, 6)).astype(np.float64)
+    tau = np.array([20.0, 12.0, 6.0, 30.0, 80.0, 50.0]); wts = np.array([0.2, 0.18, 0.14, 0.14, 0.17, 0.17])
+    sigma = b.codecomp_chunk_structure_scores(feats, tau, wts)
+    np.testing.assert_allclose(sigma, orc.chunk_structure_score(feats, tau, wts), rtol=1e-14)
+    lens = g.integers(128, 4097, size=9)
+    kw = dict(ratio=0.4, m_min=0.5, m_max=1.5, r_max=0.9, eps=1e-6)
+    got = b.codecomp_chunk_budgets(sigma, lens, window=0, **kw)
+    assert np.array_equal(got, orc.chunk_budgets(sigma, lens, **kw))
+    # equal scores -> multiplier midway; the window clamp only ever raises a budget, the chunk length caps it
+    got = b.codecomp_chunk_budgets(np.ones(3), [1000, 100, 70], window=64, **kw)
+    assert list(got) == [400, 64, 64]
+    got = b.codecomp_chunk_budgets([0.0, 1.0], [100, 100], ratio=2.0, m_min=0.5, m_max=1.5, r_max=5.0, eps=1e-6, window=8)
+    assert list(got) == [100, 100]
+    with pytest.raises(b.CodecompError):
+        b.codecomp_chunk_budgets(np.ones(2), [10, 10], window=11, **kw)
+    with pytest.raises(b.CodecompError):
+        b.codecomp_chunk_structure_scores(feats, np.zeros(6), wts)

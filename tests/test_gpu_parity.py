@@ -145,3 +145,73 @@ def test_strided_kv_and_output():
     assert torch.equal(prob.scores, ref.scores) and torch.equal(prob.idx, ref.idx)
     assert torch.equal(prob.k_out.permute(0, 2, 1, 3), ref.k_out)
     assert torch.equal(prob.v_out.permute(0, 2, 1, 3), ref.v_out)
+
+
+# ------------------------------------------------------------------ two-stage selection, structure score
+
+def run_two_stage(w, ratio, bmin, fused=True):
+    import torch
+    b = _binding()
+    q, k, v, prior = wl.make_all(w)
+    prob = b.DeviceProblem(w, q, k, v, prior, select_mode=1, span_budget_ratio=ratio, span_budget_min=bmin)
+    if fused:
+        prob.compress()
+    else:
+        prob.score(); prob.select(); prob.gather()
+    torch.cuda.synchronize()
+    sc = prob.scores.cpu().numpy(); idx = prob.idx.cpu().numpy()
+    cu, cb = w.cu_seqlens(), w.cu_budgets()
+    ratio32 = float(np.float32(ratio))
+    # scores are the pooled attention alone (no prior term) ...
+    ref = orc.score_packed(q, k, prior, cu, pool_kernel=w.pool_kernel, prior_weight=0.0)
+    pu.assert_scores_close(sc, ref)
+    # ... the selection is integer work: the oracle's rule on the GPU's own fp32 scores, bit for bit
+    for l in range(w.n_layers):
+        for r in range(w.n_seqs):
+            a, e = cu[r], cu[r + 1]
+            want = orc.select_two_stage(sc[l, :, a:e].astype(np.float64), prior[a:e], w.window, w.budgets[r],
+                                        span_ratio=ratio32, span_min=bmin)
+            assert np.array_equal(idx[l, :, cb[r]:cb[r + 1]].astype(np.int64), want), (l, r)
+    assert np.array_equal(b.DeviceProblem.bits(prob.k_out), pu.host_gather(k, idx, cu, cb))
+    assert np.array_equal(b.DeviceProblem.bits(prob.v_out), pu.host_gather(v, idx, cu, cb))
+    return prob, idx, prior
+
+
+@pytest.mark.parametrize("ratio,bmin", [(0.5, 0), (1.0, 0), (0.0, 0), (0.25, 40), (0.5, 100000)])
+def test_two_stage_selection(ratio, bmin):
+    run_two_stage(wl.scaled(wl.qwen7b_32k(), n_layers=2, seqlens=[5000]), ratio, bmin)                 # graded prior
+    run_two_stage(wl.scaled(wl.long_128k(), n_layers=1, seqlens=[4100], n_kv_heads=2, n_q_heads=14), ratio, bmin,
+                  fused=False)                                                                          # binary prior, many ties
+    run_two_stage(wl.scaled(wl.ragged_agentic(), seqlens=[700, 1300, 64, 2049, 65], budgets=[70, 130, 64, 204, 65]),
+                  ratio, bmin)
+
+
+def test_two_stage_keeps_more_structure_than_attention_alone():
+    import torch
+    b = _binding()
+    w = wl.scaled(wl.qwen7b_32k(), n_layers=2, seqlens=[6000, 3000], budgets=[480, 240])
+    prob, idx, prior = run_two_stage(w, 0.5, 0)
+    out = torch.empty((w.n_layers, w.n_kv_heads, w.n_seqs), dtype=torch.float32, device="cuda:0")
+    b.codecomp_structure_score(prob.idx, prob.prior, prob.params, out); torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    cu, cb = w.cu_seqlens(), w.cu_budgets()
+    for l in range(w.n_layers):
+        for r in range(w.n_seqs):
+            ref = orc.structure_score(idx[l, :, cb[r]:cb[r + 1]], prior[cu[r]:cu[r + 1]], w.seqlens[r])
+            np.testing.assert_allclose(got[l, :, r], ref, rtol=1e-6)
+    # attention-only selection on the same inputs retains fewer marked tokens
+    w0 = wl.scaled(w, prior_weight=0.0)
+    prob0, _, _ = run_case(w0, check_oracle=False)
+    out0 = torch.empty_like(out)
+    b.codecomp_structure_score(prob0.idx, prob0.prior, prob0.params, out0); torch.cuda.synchronize()
+    assert (out0.cpu().numpy() < got).all()
+
+
+def test_structure_score_without_marked_tokens_is_nan():
+    import torch
+    b = _binding()
+    w = wl.scaled(wl.tiny(), flag_rate=0.0)
+    prob, _, _ = run_case(w, check_oracle=False)
+    out = torch.zeros((1, 4, 1), dtype=torch.float32, device="cuda:0")
+    b.codecomp_structure_score(prob.idx, prob.prior, prob.params, out); torch.cuda.synchronize()
+    assert torch.isnan(out).all()

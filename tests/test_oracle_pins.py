@@ -319,3 +319,112 @@ def test_packed_requests_and_layers_are_independent():
     # scores of the tiny synthetic recipe have the expected magnitudes: mass W per head before pooling
     u = orc.window_attention_mass(orc.bf16_bits_to_f64(q[0, 0]), orc.bf16_bits_to_f64(k[0, :, :90]))
     np.testing.assert_allclose(u.sum(axis=1), 8.0, rtol=1e-12)
+
+
+# ------------------------------------------------------------------ budgets (eq. of the budget-allocation section)
+
+def test_log_norm_closed_forms():
+    # Norm(0) = 0, Norm(tau) = 1, saturates above tau, Norm(sqrt(1+tau)-1) = 1/2
+    tau = 15.0
+    np.testing.assert_allclose(orc.log_norm([0.0, tau, 10 * tau, math.sqrt(1 + tau) - 1], tau), [0, 1, 1, 0.5], atol=1e-15)
+    s = orc.chunk_structure_score([[0, 15.0], [15.0, 0]], [15.0, 15.0], [0.25, 0.75])
+    np.testing.assert_allclose(s, [0.75, 0.25], atol=1e-15)
+
+
+def test_budgets_closed_forms():
+    lens = np.array([1000, 2000, 512])
+    # all scores equal -> normalised score 0.5 -> multiplier midway -> B = floor(len * r * 1.0)
+    b = orc.chunk_budgets([3.0, 3.0, 3.0], lens, ratio=0.4, m_min=0.5, m_max=1.5, r_max=1.0, eps=1e-6)
+    assert list(b) == [400, 800, 204]
+    # extremes get m_min / m_max, the middle one interpolates linearly
+    b = orc.chunk_budgets([0.0, 1.0, 0.5], lens, ratio=0.4, m_min=0.5, m_max=1.5, r_max=1.0, eps=1e-6)
+    assert list(b) == [200, 1200, math.floor(512 * 0.4)]
+    # the cap r_max binds
+    b = orc.chunk_budgets([0.0, 1.0], [1000, 1000], ratio=0.6, m_min=0.5, m_max=1.5, r_max=0.8, eps=1e-6)
+    assert list(b) == [300, 800]
+    # a spread below eps is divided by eps, not by itself
+    b = orc.chunk_budgets([0.0, 1e-9], [1000, 1000], ratio=0.5, m_min=0.5, m_max=1.5, r_max=1.0, eps=1e-6)
+    assert list(b) == [250, math.floor(1000 * 0.5 * (0.5 + 1e-3))]
+    # monotone in sigma
+    g = np.random.default_rng(3)
+    sig = g.random(20); ln = np.full(20, 4096)
+    b = orc.chunk_budgets(sig, ln, ratio=0.4, m_min=0.5, m_max=1.5, r_max=1.0, eps=1e-6)
+    assert (np.diff(b[np.argsort(sig)]) >= 0).all()
+
+
+def test_structure_score_closed_forms():
+    prior = np.array([0, 1, 1, 0, 0.5, 0, 0, 2.0])
+    idx = np.array([[1, 2, 6, 7], [0, 3, 5, 6], [1, 2, 4, 7]])
+    np.testing.assert_allclose(orc.structure_score(idx, prior, 8), [0.75, 0.0, 1.0])
+    assert np.isnan(orc.structure_score(idx, np.zeros(8), 8)).all()
+
+
+# ------------------------------------------------------------------ two-stage rule (structure first, attention fills)
+
+def test_span_budget_closed_forms():
+    assert orc.span_budget(100, 0.5, 0) == 50
+    assert orc.span_budget(100, 0.5, 70) == 70        # the minimum binds
+    assert orc.span_budget(100, 0.5, 170) == 100      # never more than the budget itself
+    assert orc.span_budget(101, 0.5, 0) == 50         # floor
+    assert orc.span_budget(100, 0.0, 0) == 0
+
+
+def test_two_stage_hand_example():
+    # prefix of 8 tokens + window of 2; budget 7 -> 5 prefix slots; rho = 0.6 -> span budget 3
+    pooled = np.array([[0.10, 0.90, 0.20, 0.80, 0.30, 0.70, 0.40, 0.60, 0.0, 0.0]])
+    prior = np.array([0.0, 0.0, 1.0, 0.0, 2.0, 0.0, 1.0, 1.0, 5.0, 0.0])   # the window's own prior is ignored
+    # stage 1: largest prior 4, then the ties at 1.0 in sequence order: 2, 6 (7 does not fit)
+    # stage 2: two slots by attention among {0,1,3,5,7}: 1 (0.9), 3 (0.8)
+    got = orc.select_two_stage(pooled, prior, 2, 7, span_ratio=0.6, span_min=0)
+    assert list(got[0]) == [1, 2, 3, 4, 6, 8, 9]
+    # a zero span budget is attention only; a full one with few marked tokens keeps them all
+    assert np.array_equal(orc.select_two_stage(pooled, prior, 2, 7, span_ratio=0.0, span_min=0),
+                          orc.select(pooled, 2, 7))
+    got = orc.select_two_stage(pooled, prior, 2, 8, span_ratio=1.0, span_min=0)
+    assert list(got[0]) == [1, 2, 3, 4, 6, 7, 8, 9]
+
+
+def test_two_stage_equals_additive_limit_for_binary_prior():
+    # binary prior, span budget = whole budget: "protected first, attention fills the rest" is the
+    # lambda -> infinity limit of the additive reading as long as the marked tokens fit
+    g = np.random.default_rng(21)
+    q, k = rand_qk(4, 2, 4, 150, 8, seed=22)
+    n, w = 150, 4
+    prior = (g.random(n) < 0.15).astype(np.float64)
+    att = orc.score(q, k, prior, pool_kernel=5, prior_weight=0.0)
+    f = int((prior[: n - w] > 0).sum())
+    b = w + f + 11
+    two = orc.select_two_stage(att, prior, w, b, span_ratio=1.0, span_min=0)
+    add = orc.select(orc.fuse_prior(att, prior, 100.0 * att.max()), w, b)
+    assert np.array_equal(two, add)
+    # more marked tokens than slots: the paper keeps the FIRST marked tokens in sequence, not the best attended
+    b2 = w + f - 5
+    two = orc.select_two_stage(att, prior, w, b2, span_ratio=1.0, span_min=0)
+    marked = np.flatnonzero(prior[: n - w] > 0)
+    for hh in range(2):
+        assert list(two[hh, : b2 - w]) == list(marked[: f - 5])
+
+
+def test_two_stage_invariants_and_optimality():
+    g = np.random.default_rng(23)
+    for trial in range(6):
+        n = int(g.integers(20, 120)); w = int(g.integers(1, 6)); b = int(g.integers(w, n + 1))
+        pooled = g.random((2, n)); prior = np.where(g.random(n) < 0.3, g.random(n), 0.0)
+        rho = float(g.choice([0.0, 0.25, 0.5, 1.0])); bmin = int(g.integers(0, 5))
+        idx = orc.select_two_stage(pooled, prior, w, b, span_ratio=rho, span_min=bmin)
+        npre, bp = n - w, b - w
+        marked = set(np.flatnonzero(prior[:npre] > 0).tolist())
+        bs = orc.span_budget(bp, rho, bmin)
+        for hh in range(2):
+            row = idx[hh]
+            assert (np.diff(row) > 0).all() and np.array_equal(row[bp:], np.arange(npre, n))
+            chosen = set(row[:bp].tolist())
+            # some set P of min(bs, |marked|) marked tokens is inside, every marked token left out of P has a
+            # prior no larger than the smallest prior in P, and the rest is the attention top of the complement
+            kept_marked = sorted(chosen & marked, key=lambda j: (-prior[j], j))
+            npro = min(bs, len(marked))
+            assert len(kept_marked) >= npro
+            best = sorted(marked, key=lambda j: (-prior[j], j))[:npro]
+            assert set(best) <= chosen
+            rest = sorted(set(range(npre)) - set(best), key=lambda j: (-pooled[hh, j], j))[: bp - npro]
+            assert chosen == set(best) | set(rest)
