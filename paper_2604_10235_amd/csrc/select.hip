@@ -2,11 +2,13 @@
 // of the prefix [0, N - W); equal scores go to the lower index; indices come out ascending
 // ("retain the top-ranked context tokens ... up to the remaining chunk budget").
 //
-// One workgroup owns one problem.  An MSB-first radix select over order-preserving integer
-// images of the float scores (digits of 11, 11 and 10 bits, LDS histogram) finds the score of
-// the last admitted token and how many tokens tied at that score are admitted; one ordered
-// pass (workgroup prefix sums of "sure" and "tied" flags) then writes the indices already
-// sorted.  The score row (<= 512 KB) stays in L2 between passes.
+// One workgroup of 1024 threads owns one problem.  An MSB-first radix select over order-preserving
+// integer images of the float scores (digits of 11, 11 and 10 bits, LDS histogram) finds the score
+// of the last admitted token and how many tokens tied at that score are admitted; one ordered pass
+// (workgroup prefix sums of "sure" and "tied" flags) then writes the indices already sorted.
+// The candidates are read from memory ONCE, all loads in flight together, and stay in registers
+// through the three digit passes and the ordered pass (up to 64 per thread, N - W <= 65536); longer
+// requests fall back to re-reading the score row, which then lives in L2.
 //
 // Two selection rules share these pieces:
 //   additive   : one selection on c = pooled attention + lambda * prior (the score kernel's output);
@@ -27,6 +29,9 @@ __device__ __forceinline__ uint32_t order_key(float x) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+constexpr int kSelTileItems = 4;    // consecutive candidates per thread inside one ordered tile
+constexpr int kSelTile = kSelectThreads * kSelTileItems;
+
 struct SelectShared {
   unsigned int hist[2048];
   unsigned int prefix, need;
@@ -34,142 +39,222 @@ struct SelectShared {
   int tile_sure, tile_tie;
 };
 
-// Key of the `need`-th largest candidate among j in [0, npre) with key_at(j, key) == true, and how many
-// candidates equal to it are admitted.  Requires 1 <= need <= number of candidates.  All threads call it.
-template <class KeyAt>
-__device__ __forceinline__ void radix_select_wg(SelectShared& sh, KeyAt key_at, int npre, int need, uint32_t& tau,
-                                                int& ties) {
-  constexpr int NT = kSelectThreads;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  uint32_t prefix = 0;                   // high bits fixed so far
-  uint32_t remaining = (uint32_t)need;   // rank still to be located inside the current bucket
-  const int npad = (npre + NT - 1) / NT * NT;   // uniform trip counts: every lane takes part in the ballots
-#pragma unroll
-  for (int pass = 0; pass < 3; ++pass) {
-    const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
-    const int nbins = pass == 2 ? 1024 : 2048;
-    for (int b = tid; b < nbins; b += NT) sh.hist[b] = 0;
-    __syncthreads();
-    const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (pass == 1 ? 21 : 10));
-    constexpr int UNR = 8;                // loads in flight per thread: the pass is latency bound otherwise
-    for (int j0 = tid; j0 < npad; j0 += NT * UNR) {
-      uint32_t keys[UNR];
-      bool valid[UNR];
-#pragma unroll
-      for (int u = 0; u < UNR; ++u) {
-        const int j = j0 + u * NT;
-        keys[u] = 0u;
-        valid[u] = j < npre && key_at(j, keys[u]);
-      }
-#pragma unroll
-      for (int u = 0; u < UNR; ++u) {
-        const uint32_t key = keys[u];
-        const bool match = valid[u] && (key & himask) == prefix;
-        const uint32_t bin = (key >> shift) & (uint32_t)(nbins - 1);
-        // score distributions are concentrated: lanes that share a bin are counted with one atomic
-        // (two rounds of leader election), whatever is left falls back to one atomic per lane
-        unsigned long long pend = __ballot(match);
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-          if (pend != 0) {
-            const int leader = __ffsll(pend) - 1;
-            const uint32_t lb = __shfl(bin, leader);
-            const unsigned long long same = __ballot(match && bin == lb) & pend;
-            if (lane == leader) atomicAdd(&sh.hist[lb], (unsigned int)__popcll(same));
-            pend &= ~same;
-          }
-        }
-        if ((pend >> lane) & 1ull) atomicAdd(&sh.hist[bin], 1u);
-      }
-    }
-    __syncthreads();
-    if (wave == 0) {
-      // lane owns bins [lane*per, lane*per+per); walk from the top bin down until `remaining` is covered
-      const int per = nbins / 64;
-      unsigned int mine = 0;
-      for (int i = 0; i < per; ++i) mine += sh.hist[lane * per + i];
-      unsigned int run = mine;           // inclusive suffix sum over lanes
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const unsigned int o = __shfl_down(run, off);
-        if (lane + off < 64) run += o;
-      }
-      const unsigned int above = run - mine;   // count in bins owned by higher lanes
-      if (above < remaining && remaining <= above + mine) {   // exactly one lane
-        unsigned int acc = above;
-        int bin = per - 1;
-        for (; bin > 0; --bin) {
-          const unsigned int cnt = sh.hist[lane * per + bin];
-          if (acc + cnt >= remaining) break;
-          acc += cnt;
-        }
-        sh.prefix = prefix | ((uint32_t)(lane * per + bin) << shift);
-        sh.need = remaining - acc;       // rank inside the chosen bin
-      }
-    }
-    __syncthreads();
-    prefix = sh.prefix;
-    remaining = sh.need;
+// One candidate into the digit histogram.  Score distributions are concentrated, so lanes that share a
+// bin with the first pending lane are counted with one atomic; the rest take one atomic each.
+// Every lane of the wave must call it (ballots).
+#ifndef CODECOMP_SELECT_AGGREGATE
+#define CODECOMP_SELECT_AGGREGATE 1
+#endif
+__device__ __forceinline__ void hist_add(SelectShared& sh, bool match, uint32_t bin) {
+#if CODECOMP_SELECT_AGGREGATE
+  const int lane = threadIdx.x & 63;
+  unsigned long long pend = __ballot(match);
+  if (pend != 0) {
+    const int leader = __ffsll(pend) - 1;
+    const uint32_t lb = __shfl(bin, leader);
+    const unsigned long long same = __ballot(match && bin == lb) & pend;
+    if (lane == leader) atomicAdd(&sh.hist[lb], (unsigned int)__popcll(same));
+    pend &= ~same;
   }
-  tau = prefix;
-  ties = (int)remaining;
+  if ((pend >> lane) & 1ull) atomicAdd(&sh.hist[bin], 1u);
+#else
+  if (match) atomicAdd(&sh.hist[bin], 1u);
+#endif
 }
 
-// Ordered pass over j in [0, npre): classify(j) returns 2 (admitted for sure), 1 (tied at the cut: admitted
-// while fewer than `ties` tied candidates precede it) or 0.  emit(j, admitted, pos) is called for every j
-// with pos = number of admitted candidates before j.  All threads call it.
-template <class Classify, class Emit>
-__device__ __forceinline__ void ordered_pass_wg(SelectShared& sh, Classify classify, Emit emit, int npre, int ties) {
-  constexpr int NT = kSelectThreads;
-  constexpr int NWV = NT / 64;
-  constexpr int PER = 4;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int carry_sure = 0, carry_tie = 0;
-  for (int base = 0; base < npre; base += NT * PER) {
-    const int j0 = base + tid * PER;
-    int cls[PER];
-    int nsure = 0, ntie = 0;
-#pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      const int j = j0 + e;
-      cls[e] = j < npre ? classify(j) : 0;
-      nsure += cls[e] == 2; ntie += cls[e] == 1;
-    }
-    // exclusive scan over the workgroup of (nsure, ntie)
-    int ss = nsure, st = ntie;
+__device__ __forceinline__ int pass_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
+__device__ __forceinline__ int pass_bins(int pass) { return pass == 2 ? 1024 : 2048; }
+__device__ __forceinline__ uint32_t pass_himask(int pass) {
+  return pass == 0 ? 0u : (0xFFFFFFFFu << (pass == 1 ? 21 : 10));
+}
+
+__device__ __forceinline__ void hist_clear(SelectShared& sh, int nbins) {
+  for (int b = threadIdx.x; b < nbins; b += kSelectThreads) sh.hist[b] = 0;
+  __syncthreads();
+}
+
+// After a digit pass: the bin holding the `remaining`-th largest candidate; fixes that digit in `prefix`
+// and reduces `remaining` to the rank inside the bin.  All threads call it.
+__device__ __forceinline__ void hist_pick(SelectShared& sh, int nbins, int shift, uint32_t& prefix, uint32_t& remaining) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (wave == 0) {
+    // lane owns bins [lane*per, lane*per+per); walk from the top bin down until `remaining` is covered
+    const int per = nbins / 64;
+    unsigned int mine = 0;
+    for (int i = 0; i < per; ++i) mine += sh.hist[lane * per + i];
+    unsigned int run = mine;           // inclusive suffix sum over lanes
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
-      const int os = __shfl_up(ss, off), ot = __shfl_up(st, off);
-      if (lane >= off) { ss += os; st += ot; }
+      const unsigned int o = __shfl_down(run, off);
+      if (lane + off < 64) run += o;
     }
-    if (lane == 63) { sh.wave_sure[wave] = ss; sh.wave_tie[wave] = st; }
-    __syncthreads();
-    if (wave == 0) {
-      int ws = lane < NWV ? sh.wave_sure[lane] : 0, wt = lane < NWV ? sh.wave_tie[lane] : 0;
-      int is = ws, it = wt;
-#pragma unroll
-      for (int off = 1; off < NWV; off <<= 1) {
-        const int os = __shfl_up(is, off), ot = __shfl_up(it, off);
-        if (lane >= off) { is += os; it += ot; }
+    const unsigned int above = run - mine;   // count in bins owned by higher lanes
+    if (above < remaining && remaining <= above + mine) {   // exactly one lane
+      unsigned int acc = above;
+      int bin = per - 1;
+      for (; bin > 0; --bin) {
+        const unsigned int cnt = sh.hist[lane * per + bin];
+        if (acc + cnt >= remaining) break;
+        acc += cnt;
       }
-      if (lane < NWV) { sh.wave_sure[lane] = is - ws; sh.wave_tie[lane] = it - wt; }
-      if (lane == NWV - 1) { sh.tile_sure = is; sh.tile_tie = it; }
+      sh.prefix = prefix | ((uint32_t)(lane * per + bin) << shift);
+      sh.need = remaining - acc;       // rank inside the chosen bin
     }
-    __syncthreads();
-    int ps = carry_sure + sh.wave_sure[wave] + ss - nsure;   // sure candidates before this thread's first
-    int pt = carry_tie + sh.wave_tie[wave] + st - ntie;      // tied candidates before it
+  }
+  __syncthreads();
+  prefix = sh.prefix;
+  remaining = sh.need;
+}
+
+// Exclusive prefix counts over the workgroup for one ordered tile.  In: this thread's counts.  Out: counts
+// in lower threads of the tile, and the tile totals.  All threads call it.
+__device__ __forceinline__ void tile_scan(SelectShared& sh, int nsure, int ntie, int& before_sure, int& before_tie,
+                                          int& tot_sure, int& tot_tie) {
+  constexpr int NWV = kSelectThreads / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int ss = nsure, st = ntie;
 #pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      const int j = j0 + e;
+  for (int off = 1; off < 64; off <<= 1) {
+    const int os = __shfl_up(ss, off), ot = __shfl_up(st, off);
+    if (lane >= off) { ss += os; st += ot; }
+  }
+  if (lane == 63) { sh.wave_sure[wave] = ss; sh.wave_tie[wave] = st; }
+  __syncthreads();
+  if (wave == 0) {
+    int ws = lane < NWV ? sh.wave_sure[lane] : 0, wt = lane < NWV ? sh.wave_tie[lane] : 0;
+    int is = ws, it = wt;
+#pragma unroll
+    for (int off = 1; off < NWV; off <<= 1) {
+      const int os = __shfl_up(is, off), ot = __shfl_up(it, off);
+      if (lane >= off) { is += os; it += ot; }
+    }
+    if (lane < NWV) { sh.wave_sure[lane] = is - ws; sh.wave_tie[lane] = it - wt; }
+    if (lane == NWV - 1) { sh.tile_sure = is; sh.tile_tie = it; }
+  }
+  __syncthreads();
+  before_sure = sh.wave_sure[wave] + ss - nsure;
+  before_tie = sh.wave_tie[wave] + st - ntie;
+  tot_sure = sh.tile_sure;
+  tot_tie = sh.tile_tie;
+  __syncthreads();                      // wave_* / tile_* are rewritten by the next tile
+}
+
+// The selection proper.  A "candidate source" gives, for index j in [0, npre):
+//   key(j)      order-preserving integer image of its score,
+//   eligible(j) whether it competes in the radix select,
+//   forced(j)   whether it is admitted regardless (stage 2: members of the protected set).
+// ITEMS > 0: candidates are loaded once into registers (npre <= kSelectThreads * ITEMS);
+// ITEMS == 0: every pass re-reads them.
+// emit(j, admitted, pos) is called for every j, pos = number of admitted candidates before j.
+template <int ITEMS, class Source, class Emit>
+__device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emit, int npre, int need) {
+  constexpr int NT = kSelectThreads;
+  const int tid = threadIdx.x;
+  constexpr int NREG = ITEMS > 0 ? ITEMS : 1;
+  uint32_t keys[NREG];
+  unsigned long long elig = 0, forc = 0;       // one bit per register slot
+  // slot s of this thread holds candidate j = (s / 4) * kSelTile + tid * 4 + (s % 4): tiles in order, 4 consecutive
+  if constexpr (ITEMS > 0) {
+#pragma unroll
+    for (int s = 0; s < ITEMS; ++s) {
+      const int j = (s / kSelTileItems) * kSelTile + tid * kSelTileItems + (s % kSelTileItems);
+      keys[s] = 0u;
+      if (j < npre) {
+        keys[s] = src.key(j);
+        if (src.eligible(j)) elig |= 1ull << s;
+        if (src.forced(j)) forc |= 1ull << s;
+      }
+    }
+  }
+
+  uint32_t tau = 0xFFFFFFFFu;
+  int ties = 0;                               // need == 0: only forced candidates are admitted
+  if (need > 0) {
+    uint32_t prefix = 0, remaining = (uint32_t)need;
+#pragma unroll
+    for (int pass = 0; pass < 3; ++pass) {
+      const int shift = pass_shift(pass), nbins = pass_bins(pass);
+      const uint32_t himask = pass_himask(pass);
+      hist_clear(sh, nbins);
+      if constexpr (ITEMS > 0) {
+#pragma unroll
+        for (int s = 0; s < ITEMS; ++s) {
+          const bool match = ((elig >> s) & 1ull) && (keys[s] & himask) == prefix;
+          hist_add(sh, match, (keys[s] >> shift) & (uint32_t)(nbins - 1));
+        }
+      } else {
+        const int npad = (npre + NT - 1) / NT * NT;   // uniform trip counts: every lane takes part in the ballots
+        constexpr int UNR = 8;                        // loads in flight per thread
+        for (int j0 = tid; j0 < npad; j0 += NT * UNR) {
+          uint32_t k8[UNR];
+          bool v8[UNR];
+#pragma unroll
+          for (int u = 0; u < UNR; ++u) {
+            const int j = j0 + u * NT;
+            k8[u] = 0u; v8[u] = false;
+            if (j < npre) { k8[u] = src.key(j); v8[u] = src.eligible(j); }
+          }
+#pragma unroll
+          for (int u = 0; u < UNR; ++u)
+            hist_add(sh, v8[u] && (k8[u] & himask) == prefix, (k8[u] >> shift) & (uint32_t)(nbins - 1));
+        }
+      }
+      hist_pick(sh, nbins, shift, prefix, remaining);
+    }
+    tau = prefix;
+    ties = (int)remaining;
+  }
+
+  // ---- ordered pass
+  int carry_sure = 0, carry_tie = 0;
+  const int ntiles = (npre + kSelTile - 1) / kSelTile;
+  auto do_tile = [&](int t, const int (&cls)[kSelTileItems]) __attribute__((always_inline)) {
+    int nsure = 0, ntie = 0;
+#pragma unroll
+    for (int e = 0; e < kSelTileItems; ++e) { nsure += cls[e] == 2; ntie += cls[e] == 1; }
+    int bs, bt, ts, tt;
+    tile_scan(sh, nsure, ntie, bs, bt, ts, tt);
+    int ps = carry_sure + bs, pt = carry_tie + bt;
+#pragma unroll
+    for (int e = 0; e < kSelTileItems; ++e) {
+      const int j = t * kSelTile + tid * kSelTileItems + e;
       if (j < npre) {
         const bool admitted = cls[e] == 2 || (cls[e] == 1 && pt < ties);
         emit(j, admitted, ps + min(pt, ties));
       }
       ps += cls[e] == 2; pt += cls[e] == 1;
     }
-    carry_sure += sh.tile_sure;
-    carry_tie += sh.tile_tie;
-    __syncthreads();                      // wave_* / tile_* are rewritten by the next tile
+    carry_sure += ts; carry_tie += tt;
+  };
+  if constexpr (ITEMS > 0) {
+#pragma unroll
+    for (int t = 0; t < ITEMS / kSelTileItems; ++t) {
+      if (t < ntiles) {                        // uniform
+        int cls[kSelTileItems];
+#pragma unroll
+        for (int e = 0; e < kSelTileItems; ++e) {
+          const int s = t * kSelTileItems + e;
+          const bool el = (elig >> s) & 1ull, fo = (forc >> s) & 1ull;
+          cls[e] = fo ? 2 : (el ? (keys[s] > tau ? 2 : (keys[s] == tau ? 1 : 0)) : 0);
+        }
+        do_tile(t, cls);
+      }
+    }
+  } else {
+    for (int t = 0; t < ntiles; ++t) {
+      int cls[kSelTileItems];
+#pragma unroll
+      for (int e = 0; e < kSelTileItems; ++e) {
+        const int j = t * kSelTile + tid * kSelTileItems + e;
+        cls[e] = 0;
+        if (j < npre) {
+          if (src.forced(j)) cls[e] = 2;
+          else if (src.eligible(j)) { const uint32_t key = src.key(j); cls[e] = key > tau ? 2 : (key == tau ? 1 : 0); }
+        }
+      }
+      do_tile(t, cls);
+    }
   }
 }
 
@@ -186,7 +271,28 @@ struct SelectArgs {
   int span_min;
 };
 
+struct ScoreSource {            // additive rule: every prefix token competes on its fused score
+  const float* sc;
+  __device__ uint32_t key(int j) const { return order_key(sc[j]); }
+  __device__ bool eligible(int) const { return true; }
+  __device__ bool forced(int) const { return false; }
+};
+struct PriorSource {            // two-stage, stage 1: marked tokens compete on their prior
+  const float* p;
+  __device__ uint32_t key(int j) const { return order_key(p[j]); }
+  __device__ bool eligible(int j) const { return p[j] > 0.f; }
+  __device__ bool forced(int) const { return false; }
+};
+struct FillSource {             // two-stage, stage 2: protected tokens are in, the others compete on attention
+  const float* sc;
+  const uint8_t* member;
+  __device__ uint32_t key(int j) const { return order_key(sc[j]); }
+  __device__ bool eligible(int j) const { return member[j] == 0; }
+  __device__ bool forced(int j) const { return member[j] != 0; }
+};
+
 // additive rule: one selection on the fused scores
+template <int ITEMS>
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   constexpr int NT = kSelectThreads;
   __shared__ SelectShared sh;
@@ -199,7 +305,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   const int budget = a.cu_budgets[seq + 1] - o0;
   const int npre = n - a.W;              // candidates
   const int need = budget - a.W;         // how many of them are kept
-  const float* sc = a.scores + (int64_t)lz * a.T + s0;
   int32_t* out = a.idx + (int64_t)lz * a.TB + o0;
 
   // the observation window is always kept
@@ -209,14 +314,13 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
     for (int j = tid; j < npre; j += NT) out[j] = j;
     return;
   }
-  uint32_t tau; int ties;
-  radix_select_wg(sh, [&](int j, uint32_t& key) { key = order_key(sc[j]); return true; }, npre, need, tau, ties);
-  ordered_pass_wg(sh,
-                  [&](int j) { const uint32_t key = order_key(sc[j]); return key > tau ? 2 : (key == tau ? 1 : 0); },
-                  [&](int j, bool admitted, int pos) { if (admitted) out[pos] = j; }, npre, ties);
+  if (ITEMS > 0 && npre > NT * ITEMS) return;   // the host picks ITEMS from the longest request: cannot happen
+  ScoreSource src = {a.scores + (int64_t)lz * a.T + s0};
+  select_wg<ITEMS>(sh, src, [&](int j, bool admitted, int pos) { if (admitted) out[pos] = j; }, npre, need);
 }
 
 // two-stage rule, stage 1: once per request (the prior is shared by layers and heads)
+template <int ITEMS>
 __global__ __launch_bounds__(kSelectThreads) void select_stage1_kernel(SelectArgs a) {
   constexpr int NT = kSelectThreads;
   __shared__ SelectShared sh;
@@ -246,24 +350,16 @@ __global__ __launch_bounds__(kSelectThreads) void select_stage1_kernel(SelectArg
   bspan = min(bp, bspan);
   const int need = min(bspan, flagged);
   if (tid == 0) a.member_count[seq] = need;
-  if (need <= 0) {
+  if (need <= 0 || (ITEMS > 0 && npre > NT * ITEMS)) {
     for (int j = tid; j < npre; j += NT) member[j] = 0;
     return;
   }
-  uint32_t tau; int ties;
-  radix_select_wg(sh, [&](int j, uint32_t& key) { const float x = p[j]; key = order_key(x); return x > 0.f; }, npre,
-                  need, tau, ties);
-  ordered_pass_wg(sh,
-                  [&](int j) {
-                    const float x = p[j];
-                    if (!(x > 0.f)) return 0;
-                    const uint32_t key = order_key(x);
-                    return key > tau ? 2 : (key == tau ? 1 : 0);
-                  },
-                  [&](int j, bool admitted, int) { member[j] = admitted ? 1 : 0; }, npre, ties);
+  PriorSource src = {p};
+  select_wg<ITEMS>(sh, src, [&](int j, bool admitted, int) { member[j] = admitted ? 1 : 0; }, npre, need);
 }
 
 // two-stage rule, stage 2: attention fills what stage 1 left
+template <int ITEMS>
 __global__ __launch_bounds__(kSelectThreads) void select_stage2_kernel(SelectArgs a) {
   constexpr int NT = kSelectThreads;
   __shared__ SelectShared sh;
@@ -277,8 +373,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_stage2_kernel(SelectArg
   const int npre = n - a.W;
   const int bp = budget - a.W;
   const int need = bp - a.member_count[seq];   // slots left for attention (>= 0)
-  const float* sc = a.scores + (int64_t)lz * a.T + s0;
-  const uint8_t* member = a.member + s0;
   int32_t* out = a.idx + (int64_t)lz * a.TB + o0;
 
   for (int t = tid; t < a.W; t += NT) out[bp + t] = npre + t;
@@ -287,25 +381,33 @@ __global__ __launch_bounds__(kSelectThreads) void select_stage2_kernel(SelectArg
     for (int j = tid; j < npre; j += NT) out[j] = j;
     return;
   }
-  uint32_t tau = 0xFFFFFFFFu; int ties = 0;    // need == 0: nothing beyond stage 1 is admitted
-  if (need > 0)
-    radix_select_wg(sh, [&](int j, uint32_t& key) { key = order_key(sc[j]); return member[j] == 0; }, npre, need, tau,
-                    ties);
-  ordered_pass_wg(sh,
-                  [&](int j) {
-                    if (member[j]) return 2;
-                    if (need <= 0) return 0;
-                    const uint32_t key = order_key(sc[j]);
-                    return key > tau ? 2 : (key == tau ? 1 : 0);
-                  },
-                  [&](int j, bool admitted, int pos) { if (admitted) out[pos] = j; }, npre, ties);
+  if (ITEMS > 0 && npre > NT * ITEMS) return;
+  FillSource src = {a.scores + (int64_t)lz * a.T + s0, a.member + s0};
+  select_wg<ITEMS>(sh, src, [&](int j, bool admitted, int pos) { if (admitted) out[pos] = j; }, npre, need);
 }
+
+// candidates kept in registers per thread, chosen from the longest request
+static int items_for(const Plan& pl) {
+  const int npre = pl.max_n - pl.W;
+  if (npre <= kSelectThreads * 8) return 8;
+  if (npre <= kSelectThreads * 32) return 32;
+  if (npre <= kSelectThreads * 64) return 64;
+  return 0;
+}
+
+#define CODECOMP_DISPATCH_ITEMS(KERNEL, GRID, ARGS)                                        \
+  switch (items_for(pl)) {                                                                 \
+    case 8: KERNEL<8><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;             \
+    case 32: KERNEL<32><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
+    case 64: KERNEL<64><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
+    default: KERNEL<0><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;            \
+  }
 
 int launch_select(const Plan& pl, const float* scores, int32_t* idx, hipStream_t stream) {
   SelectArgs a = {};
   a.scores = scores; a.cu_seqlens = pl.cu_seqlens_dev; a.cu_budgets = pl.cu_budgets_dev; a.idx = idx;
   a.n_seqs = pl.n_seqs; a.T = pl.T; a.TB = pl.TB; a.W = pl.W;
-  select_kernel<<<dim3(pl.n_seqs, pl.L * pl.Hkv), dim3(kSelectThreads), 0, stream>>>(a);
+  CODECOMP_DISPATCH_ITEMS(select_kernel, dim3(pl.n_seqs, pl.L * pl.Hkv), a)
   if (hipError_t e = hipGetLastError()) return (int)e;
   return 0;
 }
@@ -319,9 +421,9 @@ int launch_select_two_stage(const Plan& pl, const float* scores, const float* pr
   a.member_count = reinterpret_cast<int32_t*>(ws + pl.off_member_count);
   a.n_seqs = pl.n_seqs; a.T = pl.T; a.TB = pl.TB; a.W = pl.W;
   a.span_ratio = pl.span_ratio; a.span_min = pl.span_min;
-  select_stage1_kernel<<<dim3(pl.n_seqs), dim3(kSelectThreads), 0, stream>>>(a);
+  CODECOMP_DISPATCH_ITEMS(select_stage1_kernel, dim3(pl.n_seqs), a)
   if (hipError_t e = hipGetLastError()) return (int)e;
-  select_stage2_kernel<<<dim3(pl.n_seqs, pl.L * pl.Hkv), dim3(kSelectThreads), 0, stream>>>(a);
+  CODECOMP_DISPATCH_ITEMS(select_stage2_kernel, dim3(pl.n_seqs, pl.L * pl.Hkv), a)
   if (hipError_t e = hipGetLastError()) return (int)e;
   return 0;
 }
