@@ -91,6 +91,9 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   const int layer = lz / a.Hkv;
   const int head = lz - layer * a.Hkv;
 
+#ifdef CODECOMP_EXP_CLOCK
+  const long long clk0_ = __builtin_readcyclecounter(), rt0_ = __builtin_amdgcn_s_memrealtime();
+#endif
   int seq, tok0, n, local, chunk_base;
   if (!locate_chunk(a.cu_seqlens, a.n_seqs, a.chunk_keys, blockIdx.x, seq, tok0, n, local, chunk_base)) return;
   const int kstart = local * a.chunk_keys;
@@ -382,6 +385,12 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
       }
     }
   }
+#ifdef CODECOMP_EXP_CLOCK
+  if (tid == 0 && blockIdx.x == 3 && blockIdx.z == 50)
+    printf("pass %d: %lld shader cycles in %lld ticks of 100 MHz -> %.3f GHz, %d tiles\n", PASS,
+           (long long)(__builtin_readcyclecounter() - clk0_), (long long)(__builtin_amdgcn_s_memrealtime() - rt0_),
+           (double)(__builtin_readcyclecounter() - clk0_) / (double)(__builtin_amdgcn_s_memrealtime() - rt0_) * 0.1, ntiles);
+#endif
 #undef CODECOMP_GLOAD
 #undef CODECOMP_SSTORE
 }

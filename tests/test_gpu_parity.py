@@ -215,3 +215,22 @@ def test_structure_score_without_marked_tokens_is_nan():
     out = torch.zeros((1, 4, 1), dtype=torch.float32, device="cuda:0")
     b.codecomp_structure_score(prob.idx, prob.prior, prob.params, out); torch.cuda.synchronize()
     assert torch.isnan(out).all()
+
+
+def test_large_logits_stay_finite_and_accurate():
+    # keys scaled by 16 (exact in bf16): logits of several hundred, one key dominates most rows
+    import torch
+    b = _binding()
+    w = wl.scaled(wl.qwen7b_32k(), n_layers=1, seqlens=[3000], n_q_heads=8, n_kv_heads=2)
+    q, k, v, prior = wl.make_all(w)
+    kf = orc.bf16_bits_to_f64(k) * 16.0
+    k16 = wl.f32_to_bf16_bits(kf.astype(np.float32))
+    assert np.array_equal(orc.bf16_bits_to_f64(k16), kf)
+    prob = b.DeviceProblem(w, q, k16, v, prior)
+    prob.score(); torch.cuda.synchronize()
+    sc = prob.scores.cpu().numpy()
+    assert np.isfinite(sc).all()
+    ref = orc.score_packed(q, k16, prior, w.cu_seqlens(), pool_kernel=w.pool_kernel, prior_weight=w.prior_weight)
+    # masses below 1e-30 are below fp32 resolution of the sums they come from; compare the rest relatively
+    big = ref > 1e-30
+    assert (np.abs(sc[big] - ref[big]) / ref[big]).max() < 1e-3
