@@ -205,9 +205,6 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   static_assert(KS >= RING, "fragment ring");
 
   f32x16 accA0, accA1, accB0, accB1;
-  // the first phase consumes a sub-tile that does not exist: -inf logits add nothing to any sum
-#pragma unroll
-  for (int v = 0; v < 16; ++v) { accB0[v] = -INFINITY; accB1[v] = -INFINITY; }
   u32x4 ring[RING];
 
   auto kfrag_ptr = [&](int buf, int kh, int ks) __attribute__((always_inline)) {
@@ -228,16 +225,22 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   };
 
   // Softmax state of the sub-tile being consumed.
-  float s0, s1, mc0, mc1, al0, al1, mn0, mn1, t0, t1;
-  // pass 1 spends the first quarter of the micro-steps on the row maxima, the rest on the exponentials
-  constexpr int MAXSTEPS = PASS == 1 ? MS / 4 : 0;
-  constexpr int EXPSTEPS = MS - MAXSTEPS;
-  constexpr int EBASE = 32 / EXPSTEPS, EEXTRA = 32 % EXPSTEPS;
+  float s0, s1, mc0 = 0.f, mc1 = 0.f, al0, al1, mn0, mn1, t0, t1;
+  // Pass 1 comes in two flavours.  FAST keeps one fixed reference per lane and row block (the largest
+  // logit of the first sub-tile) instead of a running maximum: no max3 chain, no rescaling.  A later
+  // logit more than ~88 nats above that reference would overflow fp32; the workgroup then notices the
+  // non-finite sum and redoes its chunk with the running maximum (SAFE).
+  // SAFE spends the first quarter of the micro-steps on the row maxima, the rest on the exponentials.
+  constexpr int MAXSTEPS_SAFE = MS / 4;
 
   // One micro-step of softmax work on the finished sub-tile (p0, p1).
-  auto soft_step = [&](const f32x16& p0, const f32x16& p1, int m) __attribute__((always_inline)) {
+  auto soft_step = [&](const f32x16& p0, const f32x16& p1, int m, auto fast) __attribute__((always_inline)) {
+    constexpr bool TRACK_MAX = PASS == 1 && !decltype(fast)::value;
+    constexpr int MAXSTEPS = TRACK_MAX ? MAXSTEPS_SAFE : 0;
+    constexpr int EXPSTEPS = MS - MAXSTEPS;
+    constexpr int EBASE = 32 / EXPSTEPS, EEXTRA = 32 % EXPSTEPS;
     if (m == 0) { s0 = 0.f; s1 = 0.f; }
-    if constexpr (PASS == 1) {
+    if constexpr (TRACK_MAX) {
       if (m < MAXSTEPS) {
         constexpr int PER = 16 / MAXSTEPS;      // logits of each row block folded into the maxima per step
         if (m == 0) { t0 = m_run0; t1 = m_run1; }
@@ -270,25 +273,32 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
       }
     }
   };
-  auto soft_end = [&](int ptile, int pkh) __attribute__((always_inline)) {
+  auto soft_end = [&](int ptile, int pkh, auto fast) __attribute__((always_inline)) {
     if constexpr (PASS == 1) {
-      l_run0 = l_run0 * al0 + s0; l_run1 = l_run1 * al1 + s1;
-      m_run0 = mn0; m_run1 = mn1;
+      if constexpr (decltype(fast)::value) {
+        l_run0 += s0; l_run1 += s1;
+      } else {
+        l_run0 = l_run0 * al0 + s0; l_run1 = l_run1 * al1 + s1;
+        m_run0 = mn0; m_run1 = mn1;
+      }
     } else {
       colbuf[ptile & 3][wave * 2 + hf][pkh * 32 + l32] = s0 + s1;
     }
   };
 
   // Scheduling pattern of one phase for the machine scheduler: per MFMA, the share of softmax work
-  // that hides behind it (pass 1: maxima in the first quarter of the phase, exponentials after).
-  constexpr int SG_MAX = PASS == 1 ? 16 / (MAXSTEPS > 0 ? MAXSTEPS : 1) + 2 : 1;   // max3 ops (+ scalars) per step
-  constexpr int SG_E = (32 + EXPSTEPS - 1) / EXPSTEPS;                             // logits per exponential step
-  auto sched_phase = [&]() __attribute__((always_inline)) {
+  // that hides behind it (SAFE pass 1: maxima in the first quarter of the phase, exponentials after).
+  auto sched_phase = [&](auto fast) __attribute__((always_inline)) {
+    constexpr bool TRACK_MAX = PASS == 1 && !decltype(fast)::value;
+    constexpr int MAXSTEPS = TRACK_MAX ? MAXSTEPS_SAFE : 0;
+    constexpr int EXPSTEPS = MS - MAXSTEPS;
+    constexpr int SG_MAX = TRACK_MAX ? 16 / (MAXSTEPS > 0 ? MAXSTEPS : 1) + 2 : 1;   // max3 ops (+ scalars) per step
+    constexpr int SG_E = (32 + EXPSTEPS - 1) / EXPSTEPS;                             // logits per exponential step
 #pragma unroll
     for (int m = 0; m < MS; ++m) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one MFMA
       if (m & 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);         // the ring refill (LDS read)
-      if (PASS == 1 && m < MAXSTEPS) {
+      if (TRACK_MAX && m < MAXSTEPS) {
         __builtin_amdgcn_sched_group_barrier(0x002, SG_MAX, 0);             // max3 chain (+ scalars)
       } else {
         __builtin_amdgcn_sched_group_barrier(0x002, SG_E, 0);               // fma
@@ -300,8 +310,9 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 
   // One tile = phase a + phase b.  MASKED (last, partial tile only) clears the logits of keys past
   // the end of the chunk before they are consumed.
-  auto tile_body = [&](int t, auto masked) __attribute__((always_inline)) {
+  auto tile_body = [&](int t, auto masked, auto fast) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked)::value;
+    constexpr bool FAST = PASS == 1 && decltype(fast)::value;
     const int buf = t & 1;
     const f32x16 zero = {0};
     // ---------------- phase a: logits of sub-tile a -> accA; softmax of accB (tile t-1, sub-tile b)
@@ -316,53 +327,79 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       accA0 = mma_step<PASS>(qf[0][ks], ring[ks % RING], ks == 0 ? zero : accA0);
-      soft_step(accB0, accB1, 2 * ks);
+      soft_step(accB0, accB1, 2 * ks, fast);
       accA1 = mma_step<PASS>(qf[1][ks], ring[ks % RING], ks == 0 ? zero : accA1);
       ring[ks % RING] = ks + RING < KS ? *kfrag_ptr(buf, 0, ks + RING) : *kfrag_ptr(buf, 1, ks + RING - KS);
-      soft_step(accB0, accB1, 2 * ks + 1);
+      soft_step(accB0, accB1, 2 * ks + 1, fast);
     }
-    soft_end(t - 1, 1);
-    sched_phase();
+    soft_end(t - 1, 1, fast);
+    sched_phase(fast);
     if constexpr (MASKED) mask_tail(accA0, accA1, 0);
+    if constexpr (FAST) {
+      if (t == 0) {                             // the chunk's fixed references: largest logit this lane sees first
+        float r0 = NEG_BIG, r1 = NEG_BIG;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { r0 = fmaxf(r0, accA0[v]); r1 = fmaxf(r1, accA1[v]); }
+        m_run0 = r0; m_run1 = r1;
+        mc0 = r0 * c; mc1 = r1 * c;
+      }
+    }
     // ---------------- phase b: logits of sub-tile b -> accB; softmax of accA (tile t, sub-tile a)
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       if (ks == BAR_KS) lds_barrier();          // tile t+1 is now complete in LDS buffer buf^1
       accB0 = mma_step<PASS>(qf[0][ks], ring[ks % RING], ks == 0 ? zero : accB0);
-      soft_step(accA0, accA1, 2 * ks);
+      soft_step(accA0, accA1, 2 * ks, fast);
       accB1 = mma_step<PASS>(qf[1][ks], ring[ks % RING], ks == 0 ? zero : accB1);
       ring[ks % RING] = ks + RING < KS ? *kfrag_ptr(buf, 1, ks + RING) : *kfrag_ptr(buf ^ 1, 0, ks + RING - KS);
-      soft_step(accA0, accA1, 2 * ks + 1);
+      soft_step(accA0, accA1, 2 * ks + 1, fast);
     }
-    soft_end(t, 0);
-    sched_phase();
+    soft_end(t, 0, fast);
+    sched_phase(fast);
     if constexpr (MASKED) mask_tail(accB0, accB1, 1);
   };
 
-  // ---- prologue: tile 0 into LDS buffer 0, tile 1 into the staging registers, first fragments
-  CODECOMP_GLOAD(kstart)
-  CODECOMP_SSTORE(0)
-  CODECOMP_GLOAD(kstart + kTileKeys)
-  lds_barrier();
+  // The whole chunk: prologue (tile 0 into LDS buffer 0, tile 1 into the staging registers, first
+  // fragments), the tiles, and the softmax of the very last sub-tile.
+  auto run_chunk = [&](auto fast) __attribute__((always_inline)) {
+    // the first phase consumes a sub-tile that does not exist: -inf logits add nothing to any sum
 #pragma unroll
-  for (int r = 0; r < RING; ++r) ring[r] = *kfrag_ptr(0, 0, r);
+    for (int v = 0; v < 16; ++v) { accB0[v] = -INFINITY; accB1[v] = -INFINITY; }
+    m_run0 = NEG_BIG; m_run1 = NEG_BIG; l_run0 = 0.f; l_run1 = 0.f; mc0 = 0.f; mc1 = 0.f;
+    CODECOMP_GLOAD(kstart)
+    CODECOMP_SSTORE(0)
+    CODECOMP_GLOAD(kstart + kTileKeys)
+    lds_barrier();
+#pragma unroll
+    for (int r = 0; r < RING; ++r) ring[r] = *kfrag_ptr(0, 0, r);
 
-  const int nplain = rem != 0 ? ntiles - 1 : ntiles;
-  for (int t = 0; t < nplain; ++t) {
+    const int nplain = rem != 0 ? ntiles - 1 : ntiles;
+    for (int t = 0; t < nplain; ++t) {
 #ifndef CODECOMP_EXP_NO_REDUCE
-    reduce_cols(t - 2);
+      reduce_cols(t - 2);
 #endif
-    tile_body(t, std::false_type{});
-  }
-  if (rem != 0) {
-    reduce_cols(ntiles - 3);
-    tile_body(ntiles - 1, std::true_type{});
-  }
-
-  // ---- drain: softmax of the very last sub-tile
+      tile_body(t, std::false_type{}, fast);
+    }
+    if (rem != 0) {
+      reduce_cols(ntiles - 3);
+      tile_body(ntiles - 1, std::true_type{}, fast);
+    }
 #pragma unroll
-  for (int m = 0; m < MS; ++m) soft_step(accB0, accB1, m);
-  soft_end(ntiles - 1, 1);
+    for (int m = 0; m < MS; ++m) soft_step(accB0, accB1, m, fast);
+    soft_end(ntiles - 1, 1, fast);
+  };
+
+  if constexpr (PASS == 1) {
+#ifndef CODECOMP_PASS1_SAFE_ONLY
+    run_chunk(std::true_type{});
+    const bool bad = !(l_run0 <= 3.0e38f) || !(l_run1 <= 3.0e38f);     // inf or NaN: a logit outran the reference
+    if (__syncthreads_or(bad)) run_chunk(std::false_type{});
+#else
+    run_chunk(std::false_type{});
+#endif
+  } else {
+    run_chunk(std::false_type{});
+  }
 
   if constexpr (PASS == 2) {
     lds_barrier();

@@ -234,3 +234,25 @@ def test_large_logits_stay_finite_and_accurate():
     # masses below 1e-30 are below fp32 resolution of the sums they come from; compare the rest relatively
     big = ref > 1e-30
     assert (np.abs(sc[big] - ref[big]) / ref[big]).max() < 1e-3
+
+
+def test_logits_that_outrun_the_first_tile_reference():
+    # the first keys of every chunk are ordinary, later keys are 64 times larger (exact in bf16): their logits
+    # exceed anything seen in the first tile by hundreds of nats, which the row statistics must survive
+    import torch
+    b = _binding()
+    w = wl.scaled(wl.qwen7b_32k(), n_layers=1, seqlens=[4500], n_q_heads=8, n_kv_heads=2)
+    q, k, v, prior = wl.make_all(w)
+    kf = orc.bf16_bits_to_f64(k)
+    kf[:, :, 700:] *= 64.0
+    kbig = wl.f32_to_bf16_bits(kf.astype(np.float32))
+    assert np.array_equal(orc.bf16_bits_to_f64(kbig), kf)
+    prob = b.DeviceProblem(w, q, kbig, v, prior)
+    prob.score(); torch.cuda.synchronize()
+    sc = prob.scores.cpu().numpy()
+    assert np.isfinite(sc).all()
+    ref = orc.score_packed(q, kbig, prior, w.cu_seqlens(), pool_kernel=w.pool_kernel, prior_weight=w.prior_weight)
+    big = ref > 1e-30
+    assert (np.abs(sc[big] - ref[big]) / ref[big]).max() < 1e-3
+    mass = (sc.astype(np.float64) - w.prior_weight * prior).sum(axis=2)
+    assert np.all(np.abs(mass - w.window) < 0.02 * w.window)
