@@ -13,6 +13,8 @@
 // per tile).  v_mfma_f32_32x32x16_bf16: the A and B fragments have the same lane layout
 // (lane%32 = row/column, lane/32 = which 8 of the 16 k values), so swapping the operands
 // transposes the output tile without touching the loads.
+#include <cstdio>
+#include <cstdlib>
 #include <type_traits>
 
 #include "plan.h"
@@ -39,6 +41,12 @@ struct ScoreArgs {
 
 #define NEG_BIG (-1.0e30f)
 
+#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+__device__ long long g_trace[2][2048][4];
+__device__ long long g_marks[2][2048][4];    // realtime at: chunk located, first tile in LDS, tile loop done, softmax tail done
+__device__ unsigned char g_simd[2048][8];     // SIMD id of each wave of a workgroup (pass 2)
+#endif
+
 __device__ __forceinline__ bf16x8 frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ bool locate_chunk(const int32_t* cu, int n_seqs, int chunk_keys, int item,
@@ -60,6 +68,10 @@ __device__ __forceinline__ bool locate_chunk(const int32_t* cu, int n_seqs, int 
 // (output lane = query row), PASS 2 the queries (output lane = key).
 template <int PASS>
 __device__ __forceinline__ f32x16 mma_step(u32x4 qfrag, u32x4 kfrag, f32x16 acc) {
+#ifdef CODECOMP_EXP_NO_MFMA
+  acc[0] += __uint_as_float(qfrag.x ^ kfrag.x) * 1e-30f;   // keeps the operand loads alive, one VALU op
+  return acc;
+#endif
   if constexpr (PASS == 1)
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(kfrag), frag(qfrag), acc, 0, 0, 0);
   else
@@ -96,6 +108,10 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 #endif
   int seq, tok0, n, local, chunk_base;
   if (!locate_chunk(a.cu_seqlens, a.n_seqs, a.chunk_keys, blockIdx.x, seq, tok0, n, local, chunk_base)) return;
+#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+  long long mark_[4] = {0, 0, 0, 0};
+  mark_[0] = __builtin_amdgcn_s_memrealtime();
+#endif
   const int kstart = local * a.chunk_keys;
   const int kend = min(n, kstart + a.chunk_keys);
   const int ntiles = (kend - kstart + kTileKeys - 1) / kTileKeys;
@@ -240,6 +256,10 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     constexpr int EXPSTEPS = MS - MAXSTEPS;
     constexpr int EBASE = 32 / EXPSTEPS, EEXTRA = 32 % EXPSTEPS;
     if (m == 0) { s0 = 0.f; s1 = 0.f; }
+#ifdef CODECOMP_EXP_NO_SOFT
+    s0 += p0[m % 16]; s1 += p1[m % 16];
+    return;
+#endif
     if constexpr (TRACK_MAX) {
       if (m < MAXSTEPS) {
         constexpr int PER = 16 / MAXSTEPS;      // logits of each row block folded into the maxima per step
@@ -370,6 +390,9 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     CODECOMP_SSTORE(0)
     CODECOMP_GLOAD(kstart + kTileKeys)
     lds_barrier();
+#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+    mark_[1] = __builtin_amdgcn_s_memrealtime();
+#endif
 #pragma unroll
     for (int r = 0; r < RING; ++r) ring[r] = *kfrag_ptr(0, 0, r);
 
@@ -384,9 +407,15 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
       reduce_cols(ntiles - 3);
       tile_body(ntiles - 1, std::true_type{}, fast);
     }
+#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+    mark_[2] = __builtin_amdgcn_s_memrealtime();
+#endif
 #pragma unroll
     for (int m = 0; m < MS; ++m) soft_step(accB0, accB1, m, fast);
     soft_end(ntiles - 1, 1, fast);
+#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+    mark_[3] = __builtin_amdgcn_s_memrealtime();
+#endif
   };
 
   if constexpr (PASS == 1) {
@@ -423,10 +452,28 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     }
   }
 #ifdef CODECOMP_EXP_CLOCK
+#if CODECOMP_EXP_CLOCK == 2     // one record per workgroup: where and when it ran
+  if (lane == 0 && PASS == 2) {
+    const int idx_ = blockIdx.z * gridDim.x + blockIdx.x;
+    if (idx_ < 2048 && wave < 8) g_simd[idx_][wave] = (unsigned char)((__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 4) & 3);
+  }
+  if (tid == 0) {
+    const int idx_ = blockIdx.z * gridDim.x + blockIdx.x;
+    if (idx_ < 2048) {
+      for (int q_ = 0; q_ < 4; ++q_) g_marks[PASS - 1][idx_][q_] = mark_[q_];
+      g_trace[PASS - 1][idx_][0] = rt0_;
+      g_trace[PASS - 1][idx_][1] = __builtin_amdgcn_s_memrealtime();
+      g_trace[PASS - 1][idx_][2] = __builtin_readcyclecounter() - clk0_;
+      g_trace[PASS - 1][idx_][3] = (long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) |
+                                   ((long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32);
+    }
+  }
+#else
   if (tid == 0 && blockIdx.x == 3 && blockIdx.z == 50)
     printf("pass %d: %lld shader cycles in %lld ticks of 100 MHz -> %.3f GHz, %d tiles\n", PASS,
            (long long)(__builtin_readcyclecounter() - clk0_), (long long)(__builtin_amdgcn_s_memrealtime() - rt0_),
            (double)(__builtin_readcyclecounter() - clk0_) / (double)(__builtin_amdgcn_s_memrealtime() - rt0_) * 0.1, ntiles);
+#endif
 #endif
 #undef CODECOMP_GLOAD
 #undef CODECOMP_SSTORE
@@ -550,6 +597,32 @@ int launch_score(const Plan& pl, const void* q, const void* k, const float* prio
   a.inv_g = 1.0f / (float)pl.G;
   int rc = pl.d == 128 ? dispatch_waves<128>(pl, a, stream, stages) : dispatch_waves<64>(pl, a, stream, stages);
   if (rc) return rc;
+#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+  if (const char* path_ = getenv("CODECOMP_TRACE_OUT")) {
+    static long long host_[2][2048][4];
+    static unsigned char simd_[2048][8];
+    static long long marks_[2][2048][4];
+    hipDeviceSynchronize();
+    hipMemcpyFromSymbol(host_, HIP_SYMBOL(g_trace), sizeof(host_));
+    hipMemcpyFromSymbol(simd_, HIP_SYMBOL(g_simd), sizeof(simd_));
+    hipMemcpyFromSymbol(marks_, HIP_SYMBOL(g_marks), sizeof(marks_));
+    if (FILE* f_ = fopen(path_, "w")) {
+      const int nwg_ = pl.total_chunks * pl.L * pl.Hkv;
+      for (int p_ = 0; p_ < 2; ++p_)
+        for (int i_ = 0; i_ < nwg_ && i_ < 2048; ++i_)
+          fprintf(f_, "T %d %d %d %lld %lld %lld %u %u\n", p_ + 1, i_ % pl.total_chunks, i_ / pl.total_chunks, host_[p_][i_][0],
+                  host_[p_][i_][1], host_[p_][i_][2], (unsigned)(host_[p_][i_][3] & 0xffffffff), (unsigned)(host_[p_][i_][3] >> 32));
+      for (int p_ = 0; p_ < 2; ++p_)
+        for (int i_ = 0; i_ < nwg_ && i_ < 2048; ++i_)
+          fprintf(f_, "M %d %lld %lld %lld %lld %lld %lld\n", p_ + 1, host_[p_][i_][0], marks_[p_][i_][0], marks_[p_][i_][1],
+                  marks_[p_][i_][2], marks_[p_][i_][3], host_[p_][i_][1]);
+      for (int i_ = 0; i_ < 24; ++i_)
+        fprintf(f_, "S %d : %d %d %d %d %d %d %d %d\n", i_ * 7, simd_[i_ * 7][0], simd_[i_ * 7][1], simd_[i_ * 7][2], simd_[i_ * 7][3],
+                simd_[i_ * 7][4], simd_[i_ * 7][5], simd_[i_ * 7][6], simd_[i_ * 7][7]);
+      fclose(f_);
+    }
+  }
+#endif
   if (!(stages & CODECOMP_STAGE_FINISH)) return 0;
 
   FinishArgs f;
