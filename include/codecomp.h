@@ -103,6 +103,17 @@ size_t codecomp_workspace_bytes(const codecomp_params* params);
 /* Host-only: validates parameters exactly as the launching calls do (0 or a CODECOMP_E* code). */
 int codecomp_validate(const codecomp_params* params);
 
+/* Host-only: how codecomp_score lays the R = (n_q_heads / n_kv_heads) * window softmax rows of the
+ * attention equation (section "Attention-based KV Cache Compression") over the wavefronts of a
+ * workgroup.  Rows are cut into row_splits groups (one workgroup each) of row_blocks blocks of 32.
+ * wave_desc[w], w < waves (array of 8): block of slot 0 | block of slot 1 << 8 | halves << 16; slot 0
+ * is computed for both 32-key halves of every 64-key tile, slot 1 for the halves in `halves` (bit 0
+ * first, bit 1 second, 0 = no slot 1).  Waves w and w + 4 share a SIMD; the layout evens out the
+ * number of (block, half) units per SIMD.  For tests and tuning.  Returns 0 or a CODECOMP_E* code;
+ * any output pointer may be NULL. */
+int codecomp_score_layout(const codecomp_params* params, int32_t* row_splits, int32_t* row_blocks,
+                          int32_t* waves, uint32_t* wave_desc);
+
 /* scores[l][h][j] = pooled_u[l][h][j] + lambda * prior[j], where u is the window attention mass
  * of the equation above averaged over the query-head group, and pooled_u its zero-padded
  * stride-1 average over pool_kernel neighbours (divisor always pool_kernel), per request.

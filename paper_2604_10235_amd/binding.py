@@ -62,6 +62,9 @@ def lib() -> C.CDLL:
         l.codecomp_workspace_bytes.argtypes = [P]
         l.codecomp_validate.restype = C.c_int
         l.codecomp_validate.argtypes = [P]
+        l.codecomp_score_layout.restype = C.c_int
+        l.codecomp_score_layout.argtypes = [P, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                            C.POINTER(C.c_uint32)]
         l.codecomp_score.restype = C.c_int
         l.codecomp_score.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_size_t,
                                      C.c_void_p]
@@ -124,6 +127,14 @@ def make_params(*, n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int
 
 def codecomp_validate(params: codecomp_params) -> int:
     return lib().codecomp_validate(C.byref(params))
+
+
+def codecomp_score_layout(params: codecomp_params):
+    """(status, row_splits, row_blocks, waves, wave_desc[8]) of the score passes for these parameters."""
+    rs, rb, nw = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    desc = (C.c_uint32 * 8)()
+    rc = lib().codecomp_score_layout(C.byref(params), C.byref(rs), C.byref(rb), C.byref(nw), desc)
+    return rc, rs.value, rb.value, nw.value, list(desc)
 
 
 def codecomp_workspace_bytes(params: codecomp_params) -> int:

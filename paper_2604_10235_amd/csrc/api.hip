@@ -25,6 +25,53 @@ static int chunk_keys_setting() {
   return cached;
 }
 
+// A wave runs on SIMD (wave % 4) of its compute unit (consecutive waves of a workgroup go to consecutive
+// SIMDs), and a score workgroup with more than four waves has a compute unit to itself.  The cost of a
+// wave is its number of (row block, half tile) units: 2 for a block it computes for both halves of every
+// tile, 1 for a block it shares with another wave.  Up to 8 blocks: pairs of blocks per wave, as many
+// waves as that takes (several such workgroups share a compute unit).  More: eight waves, one block each,
+// and the remaining blocks dealt out so that the four SIMDs carry the same number of units (+-1).
+void assign_row_blocks(Plan* pl) {
+  const int nb = pl->row_blocks;
+  for (int b = 0; b < 2 * kMaxWaves; ++b) pl->rb_holder[b][0] = pl->rb_holder[b][1] = 255;
+  for (int w = 0; w < kMaxWaves; ++w) pl->wave_desc[w] = 0;
+  auto hold = [&](int rb, int wave, int slot) {
+    uint8_t* h = pl->rb_holder[rb];
+    h[h[0] == 255 ? 0 : 1] = (uint8_t)(wave * 2 + slot);
+  };
+  if (nb <= 8) {
+    pl->waves = (nb + 1) / 2;
+    for (int w = 0; w < pl->waves; ++w) {
+      const int rb0 = 2 * w, rb1 = 2 * w + 1;
+      hold(rb0, w, 0);
+      if (rb1 < nb) { hold(rb1, w, 1); pl->wave_desc[w] = (uint32_t)rb0 | ((uint32_t)rb1 << 8) | (3u << 16); }
+      else pl->wave_desc[w] = (uint32_t)rb0;
+    }
+    return;
+  }
+  pl->waves = kMaxWaves;
+  int extra[kMaxWaves];                       // half-tile units of a second block per wave: 0, 1 or 2
+  const int units = 2 * (nb - kMaxWaves);     // 2 .. 16
+  for (int s = 0; s < 4; ++s) {
+    const int e = units / 4 + (s < units % 4 ? 1 : 0);
+    extra[s] = e < 2 ? e : 2;
+    extra[s + 4] = e - extra[s];
+  }
+  int next = kMaxWaves;                       // next block to hand out
+  for (int w = 0; w < kMaxWaves; ++w) {
+    hold(w, w, 0);
+    pl->wave_desc[w] = (uint32_t)w;
+    if (extra[w] == 2) { hold(next, w, 1); pl->wave_desc[w] |= ((uint32_t)next << 8) | (3u << 16); ++next; }
+  }
+  int pending = -1;                           // wave that took the first half of block `next`
+  for (int w = 0; w < kMaxWaves; ++w) {
+    if (extra[w] != 1) continue;
+    hold(next, w, 1);
+    if (pending < 0) { pl->wave_desc[w] |= ((uint32_t)next << 8) | (1u << 16); pending = w; }
+    else { pl->wave_desc[w] |= ((uint32_t)next << 8) | (2u << 16); pending = -1; ++next; }
+  }
+}
+
 int make_plan(const codecomp_params* p, Plan* pl) {
   if (!p) return CODECOMP_EINVAL_NULL;
   if (p->n_layers < 1 || p->n_seqs < 1 || p->n_seqs > 65535) return CODECOMP_EINVAL_SHAPE;
@@ -73,8 +120,8 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   const int max_rows = kMaxWaves * kRowsPerWave;
   pl->row_splits = (pl->R + max_rows - 1) / max_rows;
   int per = (pl->R + pl->row_splits - 1) / pl->row_splits;
-  pl->rows_per_split = (per + kRowsPerWave - 1) / kRowsPerWave * kRowsPerWave;
-  pl->waves = pl->rows_per_split / kRowsPerWave;
+  pl->row_blocks = (per + 31) / 32;
+  assign_row_blocks(pl);
   pl->chunk_keys = chunk_keys_setting();
   int64_t chunks = 0;
   for (int r = 0; r < p->n_seqs; ++r) {
@@ -102,10 +149,11 @@ int make_plan(const codecomp_params* p, Plan* pl) {
 
   // workspace: per-chunk softmax statistics, merged row normalisers, raw attention mass
   const size_t LH = (size_t)pl->L * pl->Hkv;
-  const size_t rpad = (size_t)pl->row_splits * pl->rows_per_split;
+  const size_t spad = (size_t)pl->row_splits * pl->waves * kRowsPerWave;   // statistics rows: one per wave slot row
+  const size_t lpad = (size_t)pl->row_splits * pl->row_blocks * 32;        // normaliser rows
   size_t off = 0;
-  pl->off_stats = off; off = align256(off + LH * pl->total_chunks * rpad * 2 * sizeof(float));
-  pl->off_lse = off;   off = align256(off + LH * pl->n_seqs * rpad * sizeof(float));
+  pl->off_stats = off; off = align256(off + LH * pl->total_chunks * spad * 2 * sizeof(float));
+  pl->off_lse = off;   off = align256(off + LH * pl->n_seqs * lpad * sizeof(float));
   pl->off_uraw = off;  off = align256(off + (size_t)pl->row_splits * LH * pl->T * sizeof(float));
   pl->off_member = off; off = align256(off + (size_t)pl->T);
   pl->off_member_count = off; off = align256(off + (size_t)pl->n_seqs * sizeof(int32_t));
@@ -135,6 +183,18 @@ size_t codecomp_workspace_bytes(const codecomp_params* params) {
 int codecomp_validate(const codecomp_params* params) {
   Plan pl;
   return make_plan(params, &pl);
+}
+
+int codecomp_score_layout(const codecomp_params* params, int32_t* row_splits, int32_t* row_blocks,
+                          int32_t* waves, uint32_t* wave_desc) {
+  Plan pl;
+  if (int rc = make_plan(params, &pl)) return rc;
+  if (row_splits) *row_splits = pl.row_splits;
+  if (row_blocks) *row_blocks = pl.row_blocks;
+  if (waves) *waves = pl.waves;
+  if (wave_desc)
+    for (int w = 0; w < kMaxWaves; ++w) wave_desc[w] = w < pl.waves ? pl.wave_desc[w] : 0u;
+  return CODECOMP_OK;
 }
 
 int codecomp_score(const void* q_obs, const void* k, const float* prior, const codecomp_params* params,

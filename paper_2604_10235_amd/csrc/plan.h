@@ -8,7 +8,7 @@
 
 namespace codecomp {
 
-constexpr int kRowsPerWave = 64;      // query rows (window x group) owned by one wavefront
+constexpr int kRowsPerWave = 64;      // query rows (window x group) one wavefront can own: two blocks of 32
 constexpr int kMaxWaves = 8;          // wavefronts per workgroup in the score kernels
 constexpr int kTileKeys = 64;         // keys staged through LDS per pipeline step
 constexpr int kSelectThreads = 1024;  // one workgroup per (layer, head, request) in select
@@ -22,8 +22,13 @@ struct Plan {
   int max_n;                 // longest request
   int R;                     // G * W softmax rows per (layer, KV head, request)
   int row_splits;            // workgroups along the row axis (each <= kMaxWaves * kRowsPerWave rows)
-  int rows_per_split;        // multiple of kRowsPerWave
-  int waves;                 // rows_per_split / kRowsPerWave
+  int row_blocks;            // blocks of 32 rows per split
+  int waves;                 // wavefronts per workgroup of the score passes
+  // Which row blocks each wave computes: block of slot 0 | block of slot 1 << 8 | halves << 16, where
+  // slot 0 covers both 32-key halves of every tile and `halves` (bit 0 first, bit 1 second) says which
+  // ones slot 1 covers (0: the wave has no slot 1).
+  uint32_t wave_desc[kMaxWaves];
+  uint8_t rb_holder[2 * kMaxWaves][2];   // per row block: wave * 2 + slot of its (one or two) owners, 255 = none
   int chunk_keys;            // keys handled by one workgroup of the score passes
   int total_chunks;          // sum over requests of ceil(N_r / chunk_keys)
   int64_t q_sl, q_ss, q_sh, q_st;
@@ -34,6 +39,9 @@ struct Plan {
   // workspace layout (byte offsets, each 256-byte aligned)
   size_t off_stats, off_lse, off_uraw, off_member, off_member_count, ws_bytes;
 };
+
+// Spreads `row_blocks` blocks over the waves of a workgroup (fills waves, wave_desc, rb_holder).
+void assign_row_blocks(Plan* plan);
 
 // Validates `p` and fills `plan`.  Returns 0 or a CODECOMP_E* code.  Host only, no HIP calls.
 int make_plan(const codecomp_params* p, Plan* plan);

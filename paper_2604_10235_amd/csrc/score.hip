@@ -8,9 +8,14 @@
 //   merge   per-row log2-sum-exp over the chunks of a request
 //   pass 2  S tile   = Q K^T   (lane = key)        -> exp2(s*c - lse) summed over rows -> u
 //   finish  average pool over pool_kernel neighbours inside the request, add lambda * prior
-// Both passes keep the wave's 64 query rows as MFMA fragments in registers for the whole
+// Both passes keep a wave's query rows as MFMA fragments in registers for the whole
 // workgroup lifetime and stream 64-key tiles of K through LDS (double buffered, one barrier
-// per tile).  v_mfma_f32_32x32x16_bf16: the A and B fragments have the same lane layout
+// per tile).  Rows come in blocks of 32 (one MFMA tile side); a wave owns one block outright
+// (slot 0) and possibly a second one (slot 1) for both 32-key halves of every tile, for the
+// first half only or for the second half only.  Half ownership lets the host spread a block
+// count that four SIMDs cannot share evenly (14 blocks for 7 query heads x 64 window rows):
+// waves w and w+4 run on the same SIMD, and every SIMD ends up with the same number of
+// (row block, half tile) units.  v_mfma_f32_32x32x16_bf16: the A and B fragments have the same lane layout
 // (lane%32 = row/column, lane/32 = which 8 of the 16 k values), so swapping the operands
 // transposes the output tile without touching the loads.
 #include <cstdio>
@@ -30,10 +35,12 @@ struct ScoreArgs {
   const uint16_t* q;
   const uint16_t* k;
   const int32_t* cu_seqlens;
-  float* stats;   // [L*Hkv][total_chunks][rpad][2] : (max * c, sum of exp2(s*c - max*c))
-  float* lse;     // [L*Hkv][n_seqs][rpad]          : log2 sum_j exp2(s_j * c)
+  float* stats;   // [L*Hkv][total_chunks][row_splits][waves*64][2] : (max * c, sum of exp2(s*c - max*c)) per wave slot row
+  float* lse;     // [L*Hkv][n_seqs][lrows]         : log2 sum_j exp2(s_j * c), lrows = row_splits * nb * 32
   float* uraw;    // [row_splits][L*Hkv][T]         : (1/G) * sum over this split's rows of A
-  int n_seqs, Hkv, G, W, R, rows_per_split, rpad, chunk_keys, total_chunks, T;
+  int n_seqs, Hkv, G, W, R, row_splits, nb, srows, lrows, chunk_keys, total_chunks, T;
+  uint32_t wave_desc[kMaxWaves];     // row block of slot 0 | row block of slot 1 << 8 | halves of slot 1 << 16 (bit 0: first, bit 1: second)
+  uint8_t rb_holder[2 * kMaxWaves][2];   // per row block: the (wave * 2 + slot) indices that hold its statistics, 255 = none
   int64_t q_sl, q_ss, q_sh, q_st, kv_sl, kv_sh, kv_st;
   float c;        // softmax_scale * log2(e)
   float inv_g;
@@ -117,15 +124,20 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   const int ntiles = (kend - kstart + kTileKeys - 1) / kTileKeys;
   const int rem = (kend - kstart) & (kTileKeys - 1);        // keys of a partial last tile (0 = it is full)
 
-  // ---- this wave's 64 query rows as MFMA fragments
-  const int row0 = split * a.rows_per_split + wave * kRowsPerWave;
+  // ---- what this wave owns (the same for every lane: keep it in scalar registers)
+  const uint32_t desc = __builtin_amdgcn_readfirstlane(a.wave_desc[wave]);
+  const int rb_of[2] = {(int)(desc & 255u), (int)((desc >> 8) & 255u)};
+  const uint32_t halves1 = (desc >> 16) & 3u;              // halves of every tile that slot 1 computes
+  const int split_row0 = split * a.nb * 32;
+
+  // ---- this wave's query rows as MFMA fragments
   u32x4 qf[2][KS];
   {
     const uint16_t* qb = a.q + (int64_t)layer * a.q_sl + (int64_t)seq * a.q_ss;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      const int row = row0 + rb * 32 + l32;
-      const bool ok = row < a.R;
+    for (int sl = 0; sl < 2; ++sl) {
+      const int row = split_row0 + rb_of[sl] * 32 + l32;
+      const bool ok = row < a.R && (sl == 0 || halves1 != 0);
       const int g = ok ? row / a.W : 0;
       const int t = ok ? row - g * a.W : 0;
       const uint16_t* p = qb + (int64_t)(head * a.G + g) * a.q_sh + (int64_t)t * a.q_st + hf * 8;
@@ -133,7 +145,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
       for (int ks = 0; ks < KS; ++ks) {
         u32x4 v = *reinterpret_cast<const u32x4*>(p + ks * 16);     // row 0 of the group when !ok: in bounds
         if (!ok) v = u32x4{0, 0, 0, 0};
-        qf[rb][ks] = v;
+        qf[sl][ks] = v;
       }
     }
   }
@@ -175,31 +187,32 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 
   const float c = a.c;
 
-  // pass 1 state: running (max, sum) of this lane's row over the keys this lane sees
+  // pass 1 state: running (max, sum) of this lane's row over the keys this lane sees, per slot
   float m_run0 = NEG_BIG, m_run1 = NEG_BIG;
   float l_run0 = 0.f, l_run1 = 0.f;
-  // pass 2 state: -lse of the 32 rows this lane holds in the S tile
+  // pass 2 state: -lse of the 2 x 16 rows this lane holds in the S tiles
   float nl[2][16];
   if constexpr (PASS == 2) {
-    const float* lse = a.lse + ((int64_t)lz * a.n_seqs + seq) * a.rpad;
+    const float* lse = a.lse + ((int64_t)lz * a.n_seqs + seq) * a.lrows;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int sl = 0; sl < 2; ++sl)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int row = row0 + rb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-        const float x = lse[row];                 // row < rpad: in bounds; padding rows get no weight
-        nl[rb][v] = row < a.R ? -x : -INFINITY;
+        const int row = split_row0 + rb_of[sl] * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+        const float x = lse[row];                 // row < lrows: in bounds; padding rows get no weight
+        nl[sl][v] = row < a.R ? -x : -INFINITY;
       }
   }
 
   // Sum the per-wave column partials of one finished tile and store the attention mass (pass 2).
+  // The last wave does it: where the waves are unevenly loaded it is one of the light ones.
   auto reduce_cols = [&](int tile) __attribute__((always_inline)) {
     if constexpr (PASS == 2) {
-      if (tile >= 0 && tid < kTileKeys) {
+      if (tile >= 0 && wave == NW - 1) {
         float s = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW * 2; ++w) s += colbuf[tile & 3][w][tid];
-        const int key = kstart + tile * kTileKeys + tid;
+        for (int w = 0; w < NW * 2; ++w) s += colbuf[tile & 3][w][lane];
+        const int key = kstart + tile * kTileKeys + lane;
         if (key < kend) a.uraw[((int64_t)split * gridDim.z + lz) * a.T + tok0 + key] = s * a.inv_g;
       }
     }
@@ -207,15 +220,16 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 
   // ------------------------------------------------------------------------------------------
   // Software pipeline.  A tile (64 keys) is two sub-tiles (32 keys) a, b; each sub-tile is one
-  // "phase" of 2*KS MFMAs.  While the matrix core forms the logits of one sub-tile, the VALU does
-  // the softmax arithmetic on the previous one, cut into one slice per MFMA ("micro-step"); a
-  // scheduling fence after every micro-step keeps the compiler from regrouping them.  The K
-  // fragments of the next four k-steps are prefetched from LDS into a 4-entry register ring, the
-  // next tile travels global -> registers -> LDS one tile ahead, and the only workgroup barrier
-  // of a tile sits in the middle of phase b, where the first fragment of the next tile is needed.
-  // Global loads stay in flight across that barrier (it waits for LDS traffic only).
+  // "phase" of KS MFMAs per active slot.  While the matrix core forms the logits of one sub-tile,
+  // the VALU does the softmax arithmetic on the previous one, cut into 2*KS slices ("gaps", one
+  // after every MFMA position); a scheduling pattern after every phase keeps the compiler from
+  // regrouping them.  The K fragments of the next four k-steps are prefetched from LDS into a
+  // 4-entry register ring, the next tile travels global -> registers -> LDS one tile ahead, and
+  // the only workgroup barrier of a tile sits in the middle of phase b, where the first fragment
+  // of the next tile is needed.  Global loads stay in flight across that barrier (it waits for
+  // LDS traffic only).  Every wave passes the same barriers whatever it owns.
   // ------------------------------------------------------------------------------------------
-  constexpr int MS = 2 * KS;                    // micro-steps (MFMAs) per phase
+  constexpr int MS = 2 * KS;                    // gaps per phase
   constexpr int RING = 4;                       // K fragments prefetched ahead
   constexpr int BAR_KS = KS - RING;             // k-step of phase b before which the barrier sits
   static_assert(KS >= RING, "fragment ring");
@@ -230,50 +244,56 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   };
   // pass 1 only: logits of keys past the end of the chunk must not enter any row sum
-  auto mask_tail = [&](f32x16& x0, f32x16& x1, int kh) __attribute__((always_inline)) {
+  auto mask_tail = [&](f32x16& x, int kh) __attribute__((always_inline)) {
     if constexpr (PASS == 1) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int key_local = kh * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-        if (key_local >= rem) { x0[v] = -INFINITY; x1[v] = -INFINITY; }
+        if (key_local >= rem) x[v] = -INFINITY;
       }
     }
   };
 
   // Softmax state of the sub-tile being consumed.
   float s0, s1, mc0 = 0.f, mc1 = 0.f, al0, al1, mn0, mn1, t0, t1;
-  // Pass 1 comes in two flavours.  FAST keeps one fixed reference per lane and row block (the largest
-  // logit of the first sub-tile) instead of a running maximum: no max3 chain, no rescaling.  A later
-  // logit more than ~88 nats above that reference would overflow fp32; the workgroup then notices the
-  // non-finite sum and redoes its chunk with the running maximum (SAFE).
-  // SAFE spends the first quarter of the micro-steps on the row maxima, the rest on the exponentials.
+  // Pass 1 comes in two flavours.  FAST keeps one fixed reference per lane and slot (the largest
+  // logit of the first sub-tile the slot computes) instead of a running maximum: no max3 chain, no
+  // rescaling.  A later logit more than ~88 nats above that reference would overflow fp32; the
+  // workgroup then notices the non-finite sum and redoes its chunk with the running maximum (SAFE).
+  // SAFE spends the first quarter of the gaps on the row maxima, the rest on the exponentials.
   constexpr int MAXSTEPS_SAFE = MS / 4;
 
-  // One micro-step of softmax work on the finished sub-tile (p0, p1).
-  auto soft_step = [&](const f32x16& p0, const f32x16& p1, int m, auto fast) __attribute__((always_inline)) {
+  // One gap's share of the softmax work on a finished sub-tile: p0 (slot 0) and, if BOTH, p1 (slot 1).
+  auto soft_step = [&](const f32x16& p0, const f32x16& p1, int m, auto both, auto fast) __attribute__((always_inline)) {
+    constexpr bool BOTH = decltype(both)::value;
     constexpr bool TRACK_MAX = PASS == 1 && !decltype(fast)::value;
+    constexpr int NE = BOTH ? 32 : 16;          // logits per lane to consume in this phase
     constexpr int MAXSTEPS = TRACK_MAX ? MAXSTEPS_SAFE : 0;
     constexpr int EXPSTEPS = MS - MAXSTEPS;
-    constexpr int EBASE = 32 / EXPSTEPS, EEXTRA = 32 % EXPSTEPS;
+    constexpr int EBASE = NE / EXPSTEPS, EEXTRA = NE % EXPSTEPS;
     if (m == 0) { s0 = 0.f; s1 = 0.f; }
 #ifdef CODECOMP_EXP_NO_SOFT
-    s0 += p0[m % 16]; s1 += p1[m % 16];
+    s0 += p0[m % 16]; if (BOTH) s1 += p1[m % 16];
     return;
 #endif
     if constexpr (TRACK_MAX) {
       if (m < MAXSTEPS) {
-        constexpr int PER = 16 / MAXSTEPS;      // logits of each row block folded into the maxima per step
+        constexpr int PER = 16 / MAXSTEPS;      // logits of each slot folded into the maxima per gap
         if (m == 0) { t0 = m_run0; t1 = m_run1; }
 #pragma unroll
         for (int e = 0; e < PER; e += 2) {
           t0 = fmaxf(fmaxf(t0, p0[m * PER + e]), p0[m * PER + e + 1]);
-          t1 = fmaxf(fmaxf(t1, p1[m * PER + e]), p1[m * PER + e + 1]);
+          if constexpr (BOTH) t1 = fmaxf(fmaxf(t1, p1[m * PER + e]), p1[m * PER + e + 1]);
         }
         if (m == MAXSTEPS - 1) {
-          mn0 = t0; mn1 = t1;
+          mn0 = t0;
           al0 = __builtin_amdgcn_exp2f((m_run0 - mn0) * c);
-          al1 = __builtin_amdgcn_exp2f((m_run1 - mn1) * c);
-          mc0 = mn0 * c; mc1 = mn1 * c;
+          mc0 = mn0 * c;
+          if constexpr (BOTH) {
+            mn1 = t1;
+            al1 = __builtin_amdgcn_exp2f((m_run1 - mn1) * c);
+            mc1 = mn1 * c;
+          }
         }
         return;
       }
@@ -283,56 +303,63 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     const int cnt = EBASE + (x < EEXTRA ? 1 : 0);
 #pragma unroll
     for (int e = e0; e < e0 + cnt; ++e) {
-      const int v = e >> 1;
+      const int v = BOTH ? e >> 1 : e;
+      const bool second = BOTH && (e & 1);
       if constexpr (PASS == 1) {
-        if (e & 1) s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(p1[v], c, -mc1));
+        if (second) s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(p1[v], c, -mc1));
         else s0 += __builtin_amdgcn_exp2f(__builtin_fmaf(p0[v], c, -mc0));
       } else {
-        if (e & 1) s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(p1[v], c, nl[1][v]));
+        if (second) s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(p1[v], c, nl[1][v]));
         else s0 += __builtin_amdgcn_exp2f(__builtin_fmaf(p0[v], c, nl[0][v]));
       }
     }
   };
-  auto soft_end = [&](int ptile, int pkh, auto fast) __attribute__((always_inline)) {
+  auto soft_end = [&](int ptile, int pkh, auto both, auto fast) __attribute__((always_inline)) {
+    constexpr bool BOTH = decltype(both)::value;
     if constexpr (PASS == 1) {
       if constexpr (decltype(fast)::value) {
-        l_run0 += s0; l_run1 += s1;
+        l_run0 += s0;
+        if constexpr (BOTH) l_run1 += s1;
       } else {
-        l_run0 = l_run0 * al0 + s0; l_run1 = l_run1 * al1 + s1;
-        m_run0 = mn0; m_run1 = mn1;
+        l_run0 = l_run0 * al0 + s0; m_run0 = mn0;
+        if constexpr (BOTH) { l_run1 = l_run1 * al1 + s1; m_run1 = mn1; }
       }
     } else {
-      colbuf[ptile & 3][wave * 2 + hf][pkh * 32 + l32] = s0 + s1;
+      colbuf[ptile & 3][wave * 2 + hf][pkh * 32 + l32] = BOTH ? s0 + s1 : s0;
     }
   };
 
-  // Scheduling pattern of one phase for the machine scheduler: per MFMA, the share of softmax work
-  // that hides behind it (SAFE pass 1: maxima in the first quarter of the phase, exponentials after).
-  auto sched_phase = [&](auto fast) __attribute__((always_inline)) {
+  // Scheduling pattern of one phase for the machine scheduler: per gap, the MFMA that opens it (slot 0
+  // in even gaps, slot 1 in odd gaps when MF1), the ring refill, and the gap's share of softmax work
+  // (SAFE pass 1: maxima in the first quarter of the phase, exponentials after).
+  auto sched_phase = [&](auto mf1, auto both, auto fast) __attribute__((always_inline)) {
+    constexpr bool MF1 = decltype(mf1)::value, BOTH = decltype(both)::value;
     constexpr bool TRACK_MAX = PASS == 1 && !decltype(fast)::value;
+    constexpr int NE = BOTH ? 32 : 16;
     constexpr int MAXSTEPS = TRACK_MAX ? MAXSTEPS_SAFE : 0;
     constexpr int EXPSTEPS = MS - MAXSTEPS;
-    constexpr int SG_MAX = TRACK_MAX ? 16 / (MAXSTEPS > 0 ? MAXSTEPS : 1) + 2 : 1;   // max3 ops (+ scalars) per step
-    constexpr int SG_E = (32 + EXPSTEPS - 1) / EXPSTEPS;                             // logits per exponential step
+    constexpr int SG_MAX = TRACK_MAX ? (BOTH ? 2 : 1) * (8 / (MAXSTEPS > 0 ? MAXSTEPS : 1)) + 2 : 1;   // max3 ops (+ scalars) per gap
+    constexpr int SG_E = (NE + EXPSTEPS - 1) / EXPSTEPS;                                             // logits per exponential gap
 #pragma unroll
     for (int m = 0; m < MS; ++m) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one MFMA
-      if (m & 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);         // the ring refill (LDS read)
+      if (!(m & 1) || MF1) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+      if (m & 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);             // the ring refill (LDS read)
       if (TRACK_MAX && m < MAXSTEPS) {
-        __builtin_amdgcn_sched_group_barrier(0x002, SG_MAX, 0);             // max3 chain (+ scalars)
+        __builtin_amdgcn_sched_group_barrier(0x002, SG_MAX, 0);                 // max3 chain (+ scalars)
       } else {
-        __builtin_amdgcn_sched_group_barrier(0x002, SG_E, 0);               // fma
-        __builtin_amdgcn_sched_group_barrier(0x400, SG_E, 0);               // exp2
-        __builtin_amdgcn_sched_group_barrier(0x002, SG_E, 0);               // add
+        __builtin_amdgcn_sched_group_barrier(0x002, SG_E, 0);                   // fma
+        __builtin_amdgcn_sched_group_barrier(0x400, SG_E, 0);                   // exp2
+        __builtin_amdgcn_sched_group_barrier(0x002, SG_E, 0);                   // add
       }
     }
   };
 
-  // One tile = phase a + phase b.  MASKED (last, partial tile only) clears the logits of keys past
-  // the end of the chunk before they are consumed.
-  auto tile_body = [&](int t, auto masked, auto fast) __attribute__((always_inline)) {
+  // One tile = phase a + phase b.  A1 / B1: slot 1 computes sub-tile a / b.  MASKED (last, partial
+  // tile only) clears the logits of keys past the end of the chunk before they are consumed.
+  auto tile_body = [&](int t, auto masked, auto fast, auto a1, auto b1) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked)::value;
     constexpr bool FAST = PASS == 1 && decltype(fast)::value;
+    constexpr bool A1 = decltype(a1)::value, B1 = decltype(b1)::value;
     const int buf = t & 1;
     const f32x16 zero = {0};
     // ---------------- phase a: logits of sub-tile a -> accA; softmax of accB (tile t-1, sub-tile b)
@@ -347,21 +374,21 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       accA0 = mma_step<PASS>(qf[0][ks], ring[ks % RING], ks == 0 ? zero : accA0);
-      soft_step(accB0, accB1, 2 * ks, fast);
-      accA1 = mma_step<PASS>(qf[1][ks], ring[ks % RING], ks == 0 ? zero : accA1);
+      soft_step(accB0, accB1, 2 * ks, b1, fast);
+      if constexpr (A1) accA1 = mma_step<PASS>(qf[1][ks], ring[ks % RING], ks == 0 ? zero : accA1);
       ring[ks % RING] = ks + RING < KS ? *kfrag_ptr(buf, 0, ks + RING) : *kfrag_ptr(buf, 1, ks + RING - KS);
-      soft_step(accB0, accB1, 2 * ks + 1, fast);
+      soft_step(accB0, accB1, 2 * ks + 1, b1, fast);
     }
-    soft_end(t - 1, 1, fast);
-    sched_phase(fast);
-    if constexpr (MASKED) mask_tail(accA0, accA1, 0);
+    soft_end(t - 1, 1, b1, fast);
+    sched_phase(a1, b1, fast);
+    if constexpr (MASKED) { mask_tail(accA0, 0); if constexpr (A1) mask_tail(accA1, 0); }
     if constexpr (FAST) {
       if (t == 0) {                             // the chunk's fixed references: largest logit this lane sees first
         float r0 = NEG_BIG, r1 = NEG_BIG;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { r0 = fmaxf(r0, accA0[v]); r1 = fmaxf(r1, accA1[v]); }
-        m_run0 = r0; m_run1 = r1;
-        mc0 = r0 * c; mc1 = r1 * c;
+        for (int v = 0; v < 16; ++v) { r0 = fmaxf(r0, accA0[v]); if constexpr (A1) r1 = fmaxf(r1, accA1[v]); }
+        m_run0 = r0; mc0 = r0 * c;
+        if constexpr (A1) { m_run1 = r1; mc1 = r1 * c; }
       }
     }
     // ---------------- phase b: logits of sub-tile b -> accB; softmax of accA (tile t, sub-tile a)
@@ -369,19 +396,27 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     for (int ks = 0; ks < KS; ++ks) {
       if (ks == BAR_KS) lds_barrier();          // tile t+1 is now complete in LDS buffer buf^1
       accB0 = mma_step<PASS>(qf[0][ks], ring[ks % RING], ks == 0 ? zero : accB0);
-      soft_step(accA0, accA1, 2 * ks, fast);
-      accB1 = mma_step<PASS>(qf[1][ks], ring[ks % RING], ks == 0 ? zero : accB1);
+      soft_step(accA0, accA1, 2 * ks, a1, fast);
+      if constexpr (B1) accB1 = mma_step<PASS>(qf[1][ks], ring[ks % RING], ks == 0 ? zero : accB1);
       ring[ks % RING] = ks + RING < KS ? *kfrag_ptr(buf, 1, ks + RING) : *kfrag_ptr(buf ^ 1, 0, ks + RING - KS);
-      soft_step(accA0, accA1, 2 * ks + 1, fast);
+      soft_step(accA0, accA1, 2 * ks + 1, a1, fast);
     }
-    soft_end(t, 0, fast);
-    sched_phase(fast);
-    if constexpr (MASKED) mask_tail(accB0, accB1, 1);
+    soft_end(t, 0, a1, fast);
+    sched_phase(b1, a1, fast);
+    if constexpr (MASKED) { mask_tail(accB0, 1); if constexpr (B1) mask_tail(accB1, 1); }
+    if constexpr (FAST && !A1 && B1) {
+      if (t == 0) {                             // slot 1 sees its first logits here (a sub-tile b may hold no valid key at all)
+        float r1 = NEG_BIG;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) r1 = fmaxf(r1, accB1[v]);
+        m_run1 = r1; mc1 = r1 * c;
+      }
+    }
   };
 
   // The whole chunk: prologue (tile 0 into LDS buffer 0, tile 1 into the staging registers, first
   // fragments), the tiles, and the softmax of the very last sub-tile.
-  auto run_chunk = [&](auto fast) __attribute__((always_inline)) {
+  auto run_chunk = [&](auto fast, auto a1, auto b1) __attribute__((always_inline)) {
     // the first phase consumes a sub-tile that does not exist: -inf logits add nothing to any sum
 #pragma unroll
     for (int v = 0; v < 16; ++v) { accB0[v] = -INFINITY; accB1[v] = -INFINITY; }
@@ -401,33 +436,43 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 #ifndef CODECOMP_EXP_NO_REDUCE
       reduce_cols(t - 2);
 #endif
-      tile_body(t, std::false_type{}, fast);
+      tile_body(t, std::false_type{}, fast, a1, b1);
     }
     if (rem != 0) {
       reduce_cols(ntiles - 3);
-      tile_body(ntiles - 1, std::true_type{}, fast);
+      tile_body(ntiles - 1, std::true_type{}, fast, a1, b1);
     }
 #if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
     mark_[2] = __builtin_amdgcn_s_memrealtime();
 #endif
 #pragma unroll
-    for (int m = 0; m < MS; ++m) soft_step(accB0, accB1, m, fast);
-    soft_end(ntiles - 1, 1, fast);
+    for (int m = 0; m < MS; ++m) soft_step(accB0, accB1, m, b1, fast);
+    soft_end(ntiles - 1, 1, b1, fast);
 #if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
     mark_[3] = __builtin_amdgcn_s_memrealtime();
 #endif
   };
 
-  if constexpr (PASS == 1) {
+  // The wave's flavour of the pipeline.  All flavours contain the same barriers in the same order.
+  auto run_wave = [&](auto a1, auto b1) __attribute__((always_inline)) {
+    if constexpr (PASS == 1) {
 #ifndef CODECOMP_PASS1_SAFE_ONLY
-    run_chunk(std::true_type{});
-    const bool bad = !(l_run0 <= 3.0e38f) || !(l_run1 <= 3.0e38f);     // inf or NaN: a logit outran the reference
-    if (__syncthreads_or(bad)) run_chunk(std::false_type{});
+      run_chunk(std::true_type{}, a1, b1);
+      // a row that saw no key at all keeps the reference -1e30: its empty sum is 0, not a failure
+      const bool bad = !(l_run0 <= 3.0e38f) || !(l_run1 <= 3.0e38f);     // inf or NaN: a logit outran the reference
+      if (__syncthreads_or(bad)) run_chunk(std::false_type{}, a1, b1);
 #else
-    run_chunk(std::false_type{});
+      run_chunk(std::false_type{}, a1, b1);
 #endif
-  } else {
-    run_chunk(std::false_type{});
+    } else {
+      run_chunk(std::false_type{}, a1, b1);
+    }
+  };
+  switch (halves1) {
+    case 0: run_wave(std::false_type{}, std::false_type{}); break;
+    case 1: run_wave(std::true_type{}, std::false_type{}); break;
+    case 2: run_wave(std::false_type{}, std::true_type{}); break;
+    default: run_wave(std::true_type{}, std::true_type{}); break;
   }
 
   if constexpr (PASS == 2) {
@@ -435,19 +480,19 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     reduce_cols(ntiles - 2);
     reduce_cols(ntiles - 1);
   } else {
-    // merge the two half-wave views of each row, then one (max*c, sum) pair per row and chunk
-    float* st = a.stats + (((int64_t)lz * a.total_chunks + chunk_base + local) * a.rpad) * 2;
+    // merge the two half-wave views of each row, then one (max*c, sum) pair per slot row and chunk
+    float* st = a.stats + ((((int64_t)lz * a.total_chunks + chunk_base + local) * a.row_splits + split) * a.srows) * 2;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      const float m_r = rb == 0 ? m_run0 : m_run1, l_r = rb == 0 ? l_run0 : l_run1;
+    for (int sl = 0; sl < 2; ++sl) {
+      const float m_r = sl == 0 ? m_run0 : m_run1, l_r = sl == 0 ? l_run0 : l_run1;
       const float m_o = __shfl_xor(m_r, 32);
       const float l_o = __shfl_xor(l_r, 32);
       const float M = fmaxf(m_r, m_o);
       const float L = l_r * __builtin_amdgcn_exp2f((m_r - M) * c) + l_o * __builtin_amdgcn_exp2f((m_o - M) * c);
-      const int row = row0 + rb * 32 + l32;
-      if (lane < 32) {
-        st[row * 2 + 0] = M * c;
-        st[row * 2 + 1] = L;
+      const int srow = (wave * 2 + sl) * 32 + l32;
+      if (lane < 32 && (sl == 0 || halves1 != 0)) {
+        st[srow * 2 + 0] = M * c;
+        st[srow * 2 + 1] = L;
       }
     }
   }
@@ -479,23 +524,36 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 #undef CODECOMP_SSTORE
 }
 
-// One thread per (layer*head, request, row): log2-sum-exp over that request's chunks.
+// One thread per (layer*head, request, row): log2-sum-exp over that request's chunks and over the
+// (at most two) wave slots that hold a share of the row's keys.
 __global__ __launch_bounds__(256) void score_merge_kernel(ScoreArgs a) {
   const int row = blockIdx.x * blockDim.x + threadIdx.x;
   const int seq = blockIdx.y;
   const int lz = blockIdx.z;
-  if (row >= a.rpad) return;
+  if (row >= a.lrows) return;
+  const int split = row / (a.nb * 32);
+  const int rb = (row - split * a.nb * 32) >> 5;
   int chunk_base = 0;
   for (int r = 0; r < seq; ++r)
     chunk_base += (a.cu_seqlens[r + 1] - a.cu_seqlens[r] + a.chunk_keys - 1) / a.chunk_keys;
   const int nch = (a.cu_seqlens[seq + 1] - a.cu_seqlens[seq] + a.chunk_keys - 1) / a.chunk_keys;
-  const float* st = a.stats + (((int64_t)lz * a.total_chunks + chunk_base) * a.rpad + row) * 2;
+  const int64_t chunk_stride = (int64_t)a.row_splits * a.srows * 2;
+  const float* st = a.stats + (((int64_t)lz * a.total_chunks + chunk_base) * a.row_splits + split) * a.srows * 2;
   float M = NEG_BIG;
-  for (int ch = 0; ch < nch; ++ch) M = fmaxf(M, st[(int64_t)ch * a.rpad * 2]);
+  for (int h = 0; h < 2; ++h) {
+    const int holder = a.rb_holder[rb][h];
+    if (holder == 255) continue;
+    const float* sh = st + (holder * 32 + (row & 31)) * 2;
+    for (int ch = 0; ch < nch; ++ch) M = fmaxf(M, sh[ch * chunk_stride]);
+  }
   float L = 0.f;
-  for (int ch = 0; ch < nch; ++ch)
-    L += st[(int64_t)ch * a.rpad * 2 + 1] * __builtin_amdgcn_exp2f(st[(int64_t)ch * a.rpad * 2] - M);
-  a.lse[((int64_t)lz * a.n_seqs + seq) * a.rpad + row] = M + log2f(L);
+  for (int h = 0; h < 2; ++h) {
+    const int holder = a.rb_holder[rb][h];
+    if (holder == 255) continue;
+    const float* sh = st + (holder * 32 + (row & 31)) * 2;
+    for (int ch = 0; ch < nch; ++ch) L += sh[ch * chunk_stride + 1] * __builtin_amdgcn_exp2f(sh[ch * chunk_stride] - M);
+  }
+  a.lse[((int64_t)lz * a.n_seqs + seq) * a.lrows + row] = M + log2f(L);
 }
 
 struct FinishArgs {
@@ -552,7 +610,7 @@ static int launch_passes(const Plan& pl, const ScoreArgs& a, hipStream_t stream,
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
   if (stages & CODECOMP_STAGE_ROW_MERGE) {
-    const dim3 mgrid((a.rpad + 255) / 256, pl.n_seqs, pl.L * pl.Hkv);
+    const dim3 mgrid((a.lrows + 255) / 256, pl.n_seqs, pl.L * pl.Hkv);
     score_merge_kernel<<<mgrid, dim3(256), 0, stream>>>(a);
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
@@ -570,9 +628,6 @@ static int dispatch_waves(const Plan& pl, const ScoreArgs& a, hipStream_t s, uns
     case 2: return launch_passes<D, 2>(pl, a, s, st);
     case 3: return launch_passes<D, 3>(pl, a, s, st);
     case 4: return launch_passes<D, 4>(pl, a, s, st);
-    case 5: return launch_passes<D, 5>(pl, a, s, st);
-    case 6: return launch_passes<D, 6>(pl, a, s, st);
-    case 7: return launch_passes<D, 7>(pl, a, s, st);
     case 8: return launch_passes<D, 8>(pl, a, s, st);
   }
   return CODECOMP_EINVAL_SHAPE;
@@ -589,7 +644,10 @@ int launch_score(const Plan& pl, const void* q, const void* k, const float* prio
   a.lse = reinterpret_cast<float*>(ws + pl.off_lse);
   a.uraw = reinterpret_cast<float*>(ws + pl.off_uraw);
   a.n_seqs = pl.n_seqs; a.Hkv = pl.Hkv; a.G = pl.G; a.W = pl.W; a.R = pl.R;
-  a.rows_per_split = pl.rows_per_split; a.rpad = pl.row_splits * pl.rows_per_split;
+  a.row_splits = pl.row_splits; a.nb = pl.row_blocks; a.srows = pl.waves * kRowsPerWave;
+  a.lrows = pl.row_splits * pl.row_blocks * 32;
+  for (int w = 0; w < kMaxWaves; ++w) a.wave_desc[w] = pl.wave_desc[w];
+  for (int b = 0; b < 2 * kMaxWaves; ++b) { a.rb_holder[b][0] = pl.rb_holder[b][0]; a.rb_holder[b][1] = pl.rb_holder[b][1]; }
   a.chunk_keys = pl.chunk_keys; a.total_chunks = pl.total_chunks; a.T = pl.T;
   a.q_sl = pl.q_sl; a.q_ss = pl.q_ss; a.q_sh = pl.q_sh; a.q_st = pl.q_st;
   a.kv_sl = pl.kv_sl; a.kv_sh = pl.kv_sh; a.kv_st = pl.kv_st;

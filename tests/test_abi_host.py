@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
     assert {"codecomp_score", "codecomp_select", "codecomp_gather", "codecomp_compress",
             "codecomp_workspace_bytes", "codecomp_validate", "codecomp_status_string", "codecomp_version",
             "codecomp_score_stages", "codecomp_select_two_stage", "codecomp_structure_score",
-            "codecomp_chunk_budgets", "codecomp_chunk_structure_scores"} <= set(names)
+            "codecomp_chunk_budgets", "codecomp_chunk_structure_scores", "codecomp_score_layout"} <= set(names)
     lib = b.lib()
     for n in names:
         assert hasattr(lib, n), n
@@ -163,3 +163,36 @@ def test_host_budget_functions_match_oracle():
         b.codecomp_chunk_budgets(np.ones(2), [10, 10], window=11, **kw)
     with pytest.raises(b.CodecompError):
         b.codecomp_chunk_structure_scores(feats, np.zeros(6), wts)
+
+
+@pytest.mark.parametrize("group,window", [(1, 1), (1, 32), (1, 64), (4, 32), (7, 32), (4, 64), (5, 64), (6, 64), (7, 64),
+                                          (8, 64), (7, 128), (3, 100), (9, 64), (13, 40), (16, 64)])
+def test_score_layout_covers_every_row_block_once_and_evens_out_the_simds(group, window):
+    """Every (row block, half tile) unit has exactly one owner, and with more than four waves (one workgroup
+    per compute unit, waves w and w+4 on one SIMD) the four SIMDs carry the same number of units +-1."""
+    n = max(256, 2 * window)
+    p = good(n_q_heads=2 * group, n_kv_heads=2, window=window, cu_seqlens_host=np.array([0, n]),
+             cu_budgets_host=np.array([0, window + 8]))
+    rc, splits, blocks, waves, desc = b.codecomp_score_layout(p)
+    assert rc == 0
+    rows = group * window
+    assert splits == -(-rows // 512) and splits * blocks * 32 >= rows and 1 <= waves <= 8 and blocks <= 16
+    assert (blocks - 1) * 32 * splits < rows + 32 * splits          # no block beyond what the rows need
+    owners = np.zeros((blocks, 2), dtype=int)                       # owners[block][half]
+    load = np.zeros(8, dtype=int)
+    for w in range(waves):
+        rb0, rb1, halves = desc[w] & 255, (desc[w] >> 8) & 255, (desc[w] >> 16) & 3
+        assert rb0 < blocks
+        owners[rb0] += 1
+        load[w] += 2
+        for h in range(2):
+            if halves >> h & 1:
+                assert rb1 < blocks and rb1 != rb0
+                owners[rb1][h] += 1
+                load[w] += 1
+    assert (owners == 1).all()
+    assert all(d == 0 for d in desc[waves:])
+    if waves > 4:
+        simd = load[:4] + load[4:]
+        assert simd.max() - simd.min() <= 1, (desc, simd)
+        assert simd.max() == -(-2 * blocks // 4)
