@@ -10,21 +10,6 @@ namespace codecomp {
 
 static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
-static int chunk_keys_setting() {
-  // Keys per workgroup of the score passes.  CODECOMP_CHUNK_KEYS overrides the default for
-  // experiments (multiple of the LDS tile, at least one tile).
-  static int cached = 0;
-  if (cached == 0) {
-    int v = 2048;
-    if (const char* e = getenv("CODECOMP_CHUNK_KEYS")) {
-      int x = atoi(e);
-      if (x >= kTileKeys && x % kTileKeys == 0 && x <= (1 << 20)) v = x;
-    }
-    cached = v;
-  }
-  return cached;
-}
-
 // A wave runs on SIMD (wave % 4) of its compute unit (consecutive waves of a workgroup go to consecutive
 // SIMDs), and a score workgroup with more than four waves has a compute unit to itself.  The cost of a
 // wave is its number of (row block, half tile) units: 2 for a block it computes for both halves of every
@@ -122,14 +107,15 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   int per = (pl->R + pl->row_splits - 1) / pl->row_splits;
   pl->row_blocks = (per + 31) / 32;
   assign_row_blocks(pl);
-  pl->chunk_keys = chunk_keys_setting();
-  int64_t chunks = 0;
+  int64_t tiles = 0;
   for (int r = 0; r < p->n_seqs; ++r) {
     int n = p->cu_seqlens_host[r + 1] - p->cu_seqlens_host[r];
-    chunks += (n + pl->chunk_keys - 1) / pl->chunk_keys;
+    tiles += (n + kTileKeys - 1) / kTileKeys;
   }
-  if (chunks > (1 << 30)) return CODECOMP_EINVAL_SHAPE;
-  pl->total_chunks = (int)chunks;
+  const int64_t total_tiles = tiles * pl->L * pl->Hkv * pl->row_splits;
+  if (total_tiles > (1 << 30)) return CODECOMP_EINVAL_SHAPE;
+  pl->tiles_per_problem = (int)tiles;
+  pl->total_tiles = (int)total_tiles;
 
   const int64_t d = pl->d;
   pl->q_st = p->q_stride_tok ? p->q_stride_tok : d;
@@ -149,10 +135,11 @@ int make_plan(const codecomp_params* p, Plan* pl) {
 
   // workspace: per-chunk softmax statistics, merged row normalisers, raw attention mass
   const size_t LH = (size_t)pl->L * pl->Hkv;
-  const size_t spad = (size_t)pl->row_splits * pl->waves * kRowsPerWave;   // statistics rows: one per wave slot row
   const size_t lpad = (size_t)pl->row_splits * pl->row_blocks * 32;        // normaliser rows
   size_t off = 0;
-  pl->off_stats = off; off = align256(off + LH * pl->total_chunks * spad * 2 * sizeof(float));
+  // one statistics slot per segment; slot numbers stay below (workgroups + problems)
+  const size_t slots = (size_t)kMaxScoreGrid + LH * pl->row_splits * pl->n_seqs;
+  pl->off_stats = off; off = align256(off + slots * (pl->waves * kRowsPerWave) * 2 * sizeof(float));
   pl->off_lse = off;   off = align256(off + LH * pl->n_seqs * lpad * sizeof(float));
   pl->off_uraw = off;  off = align256(off + (size_t)pl->row_splits * LH * pl->T * sizeof(float));
   pl->off_member = off; off = align256(off + (size_t)pl->T);

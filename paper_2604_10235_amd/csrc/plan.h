@@ -11,6 +11,8 @@ namespace codecomp {
 constexpr int kRowsPerWave = 64;      // query rows (window x group) one wavefront can own: two blocks of 32
 constexpr int kMaxWaves = 8;          // wavefronts per workgroup in the score kernels
 constexpr int kTileKeys = 64;         // keys staged through LDS per pipeline step
+constexpr int kMaxScoreGrid = 2048;   // most workgroups a score pass is launched with
+constexpr int kMinTilesPerWorkgroup = 4;
 constexpr int kSelectThreads = 1024;  // one workgroup per (layer, head, request) in select
 
 struct Plan {
@@ -29,8 +31,8 @@ struct Plan {
   // ones slot 1 covers (0: the wave has no slot 1).
   uint32_t wave_desc[kMaxWaves];
   uint8_t rb_holder[2 * kMaxWaves][2];   // per row block: wave * 2 + slot of its (one or two) owners, 255 = none
-  int chunk_keys;            // keys handled by one workgroup of the score passes
-  int total_chunks;          // sum over requests of ceil(N_r / chunk_keys)
+  int tiles_per_problem;     // sum over requests of ceil(N_r / kTileKeys): tiles of one (layer, head, row split)
+  int total_tiles;           // L * Hkv * row_splits * tiles_per_problem, shared out evenly over the workgroups
   int64_t q_sl, q_ss, q_sh, q_st;
   int64_t kv_sl, kv_sh, kv_st;
   int64_t o_sl, o_sh, o_st;

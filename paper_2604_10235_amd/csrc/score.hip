@@ -4,8 +4,8 @@
 // keys and summed per key (the equation of section "Attention-based KV Cache Compression").
 // A column sum of a row softmax needs every row normaliser first, so the logits are formed
 // twice on the matrix cores:
-//   pass 1  S^T tile = K Q^T   (lane = query row)  -> per-row running (max, sum) -> per-chunk stats
-//   merge   per-row log2-sum-exp over the chunks of a request
+//   pass 1  S^T tile = K Q^T   (lane = query row)  -> per-row running (max, sum) -> per-segment stats
+//   merge   per-row log2-sum-exp over the segments of a request
 //   pass 2  S tile   = Q K^T   (lane = key)        -> exp2(s*c - lse) summed over rows -> u
 //   finish  average pool over pool_kernel neighbours inside the request, add lambda * prior
 // Both passes keep a wave's query rows as MFMA fragments in registers for the whole
@@ -35,10 +35,17 @@ struct ScoreArgs {
   const uint16_t* q;
   const uint16_t* k;
   const int32_t* cu_seqlens;
-  float* stats;   // [L*Hkv][total_chunks][row_splits][waves*64][2] : (max * c, sum of exp2(s*c - max*c)) per wave slot row
+  float* stats;   // [segment slot][waves*64][2] : (max * c, sum of exp2(s*c - max*c)) per wave slot row
   float* lse;     // [L*Hkv][n_seqs][lrows]         : log2 sum_j exp2(s_j * c), lrows = row_splits * nb * 32
   float* uraw;    // [row_splits][L*Hkv][T]         : (1/G) * sum over this split's rows of A
-  int n_seqs, Hkv, G, W, R, row_splits, nb, srows, lrows, chunk_keys, total_chunks, T;
+  int n_seqs, Hkv, LH, G, W, R, row_splits, nb, srows, lrows, T;
+  // Work distribution.  The 64-key tiles of all problems (layer*head, row split, request), in that order,
+  // form one sequence of total_tiles tiles; workgroup g of `wgs` takes tiles [g*total/wgs, (g+1)*total/wgs)
+  // and walks through the "segments" in which that range meets the problems.  Pass 1 leaves the statistics
+  // of the segment of workgroup g in problem p in slot g + p (distinct for distinct segments).
+  int tiles_per_problem;             // sum over requests of ceil(N_r / 64)
+  int total_tiles;                   // L*Hkv * row_splits * tiles_per_problem
+  int stat_wgs;                      // workgroups of the pass-1 launch whose statistics `stats` holds
   uint32_t wave_desc[kMaxWaves];     // row block of slot 0 | row block of slot 1 << 8 | halves of slot 1 << 16 (bit 0: first, bit 1: second)
   uint8_t rb_holder[2 * kMaxWaves][2];   // per row block: the (wave * 2 + slot) indices that hold its statistics, 255 = none
   int64_t q_sl, q_ss, q_sh, q_st, kv_sl, kv_sh, kv_st;
@@ -56,19 +63,24 @@ __device__ unsigned char g_simd[2048][8];     // SIMD id of each wave of a workg
 
 __device__ __forceinline__ bf16x8 frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-__device__ __forceinline__ bool locate_chunk(const int32_t* cu, int n_seqs, int chunk_keys, int item,
-                                             int& seq, int& tok0, int& n, int& local, int& chunk_base) {
+// Request that holds tile `xr` of a problem's tile sequence.
+__device__ __forceinline__ void locate_tile(const int32_t* cu, int n_seqs, int xr, int& seq, int& tok0, int& n,
+                                            int& tile_in_seq, int& tiles_of_seq) {
   int acc = 0;
   for (int r = 0; r < n_seqs; ++r) {
-    int a = cu[r], b = cu[r + 1];
-    int nch = (b - a + chunk_keys - 1) / chunk_keys;
-    if (item < acc + nch) {
-      seq = r; tok0 = a; n = b - a; local = item - acc; chunk_base = acc;
-      return true;
+    const int a = cu[r], b = cu[r + 1];
+    const int nt = (b - a + kTileKeys - 1) / kTileKeys;
+    if (xr < acc + nt || r == n_seqs - 1) {
+      seq = r; tok0 = a; n = b - a; tile_in_seq = xr - acc; tiles_of_seq = nt;
+      return;
     }
-    acc += nch;
+    acc += nt;
   }
-  return false;
+}
+
+// Workgroup (of `wgs`) whose tile range [g*total/wgs, (g+1)*total/wgs) holds tile x.
+__device__ __forceinline__ int wg_of_tile(int x, int total, int wgs) {
+  return (int)((((int64_t)x + 1) * wgs + total - 1) / total) - 1;
 }
 
 // MFMA helper: D = A * B + C on one 32x32x16 bf16 step.  PASS 1 puts the keys on the A side
@@ -105,30 +117,38 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   const int wave = tid >> 6;
   const int l32 = lane & 31;
   const int hf = lane >> 5;
-  const int split = blockIdx.y;
-  const int lz = blockIdx.z;               // layer * Hkv + head
-  const int layer = lz / a.Hkv;
-  const int head = lz - layer * a.Hkv;
-
 #ifdef CODECOMP_EXP_CLOCK
   const long long clk0_ = __builtin_readcyclecounter(), rt0_ = __builtin_amdgcn_s_memrealtime();
 #endif
-  int seq, tok0, n, local, chunk_base;
-  if (!locate_chunk(a.cu_seqlens, a.n_seqs, a.chunk_keys, blockIdx.x, seq, tok0, n, local, chunk_base)) return;
 #if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
   long long mark_[4] = {0, 0, 0, 0};
-  mark_[0] = __builtin_amdgcn_s_memrealtime();
+  int nseg_ = 0;
 #endif
-  const int kstart = local * a.chunk_keys;
-  const int kend = min(n, kstart + a.chunk_keys);
-  const int ntiles = (kend - kstart + kTileKeys - 1) / kTileKeys;
-  const int rem = (kend - kstart) & (kTileKeys - 1);        // keys of a partial last tile (0 = it is full)
-
   // ---- what this wave owns (the same for every lane: keep it in scalar registers)
   const uint32_t desc = __builtin_amdgcn_readfirstlane(a.wave_desc[wave]);
   const int rb_of[2] = {(int)(desc & 255u), (int)((desc >> 8) & 255u)};
   const uint32_t halves1 = (desc >> 16) & 3u;              // halves of every tile that slot 1 computes
+
+  // ---- this workgroup's share of the tile sequence, one segment (part of one problem) at a time
+  const int x_begin = (int)((int64_t)blockIdx.x * a.total_tiles / gridDim.x);
+  const int x_end = (int)((int64_t)(blockIdx.x + 1) * a.total_tiles / gridDim.x);
+  for (int x = x_begin; x < x_end;) {
+  const int hi = x / a.tiles_per_problem;                  // problem: (layer * Hkv + head) * row_splits + split
+  const int lz = hi / a.row_splits;
+  const int split = hi - lz * a.row_splits;
+  const int layer = lz / a.Hkv;
+  const int head = lz - layer * a.Hkv;
+  int seq, tok0, n, tile_in_seq, tiles_of_seq;
+  locate_tile(a.cu_seqlens, a.n_seqs, x - hi * a.tiles_per_problem, seq, tok0, n, tile_in_seq, tiles_of_seq);
+  const int ntiles = min(x_end - x, tiles_of_seq - tile_in_seq);
+  const int kstart = tile_in_seq * kTileKeys;
+  const int kend = min(n, kstart + ntiles * kTileKeys);
+  const int rem = (kend - kstart) & (kTileKeys - 1);        // keys of a partial last tile (0 = it is full)
   const int split_row0 = split * a.nb * 32;
+#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+  mark_[0] = __builtin_amdgcn_s_memrealtime();
+  ++nseg_;
+#endif
 
   // ---- this wave's query rows as MFMA fragments
   u32x4 qf[2][KS];
@@ -213,7 +233,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 #pragma unroll
         for (int w = 0; w < NW * 2; ++w) s += colbuf[tile & 3][w][lane];
         const int key = kstart + tile * kTileKeys + lane;
-        if (key < kend) a.uraw[((int64_t)split * gridDim.z + lz) * a.T + tok0 + key] = s * a.inv_g;
+        if (key < kend) a.uraw[((int64_t)split * a.LH + lz) * a.T + tok0 + key] = s * a.inv_g;
       }
     }
   };
@@ -480,8 +500,8 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     reduce_cols(ntiles - 2);
     reduce_cols(ntiles - 1);
   } else {
-    // merge the two half-wave views of each row, then one (max*c, sum) pair per slot row and chunk
-    float* st = a.stats + ((((int64_t)lz * a.total_chunks + chunk_base + local) * a.row_splits + split) * a.srows) * 2;
+    // merge the two half-wave views of each row, then one (max*c, sum) pair per slot row and segment
+    float* st = a.stats + ((int64_t)(blockIdx.x + hi * a.n_seqs + seq) * a.srows) * 2;
 #pragma unroll
     for (int sl = 0; sl < 2; ++sl) {
       const float m_r = sl == 0 ? m_run0 : m_run1, l_r = sl == 0 ? l_run0 : l_run1;
@@ -496,14 +516,18 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
       }
     }
   }
+  // the next segment reuses the LDS buffers: every wave must be done reading them
+  lds_barrier();
+  x += ntiles;
+  }   // segments
 #ifdef CODECOMP_EXP_CLOCK
 #if CODECOMP_EXP_CLOCK == 2     // one record per workgroup: where and when it ran
   if (lane == 0 && PASS == 2) {
-    const int idx_ = blockIdx.z * gridDim.x + blockIdx.x;
+    const int idx_ = blockIdx.x;
     if (idx_ < 2048 && wave < 8) g_simd[idx_][wave] = (unsigned char)((__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 4) & 3);
   }
   if (tid == 0) {
-    const int idx_ = blockIdx.z * gridDim.x + blockIdx.x;
+    const int idx_ = blockIdx.x;
     if (idx_ < 2048) {
       for (int q_ = 0; q_ < 4; ++q_) g_marks[PASS - 1][idx_][q_] = mark_[q_];
       g_trace[PASS - 1][idx_][0] = rt0_;
@@ -514,18 +538,18 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     }
   }
 #else
-  if (tid == 0 && blockIdx.x == 3 && blockIdx.z == 50)
+  if (tid == 0 && blockIdx.x == gridDim.x / 2)
     printf("pass %d: %lld shader cycles in %lld ticks of 100 MHz -> %.3f GHz, %d tiles\n", PASS,
            (long long)(__builtin_readcyclecounter() - clk0_), (long long)(__builtin_amdgcn_s_memrealtime() - rt0_),
-           (double)(__builtin_readcyclecounter() - clk0_) / (double)(__builtin_amdgcn_s_memrealtime() - rt0_) * 0.1, ntiles);
+           (double)(__builtin_readcyclecounter() - clk0_) / (double)(__builtin_amdgcn_s_memrealtime() - rt0_) * 0.1, x_end - x_begin);
 #endif
 #endif
 #undef CODECOMP_GLOAD
 #undef CODECOMP_SSTORE
 }
 
-// One thread per (layer*head, request, row): log2-sum-exp over that request's chunks and over the
-// (at most two) wave slots that hold a share of the row's keys.
+// One thread per (layer*head, request, row): log2-sum-exp over the segments that cover the request and
+// over the (at most two) wave slots that hold a share of the row's keys.
 __global__ __launch_bounds__(256) void score_merge_kernel(ScoreArgs a) {
   const int row = blockIdx.x * blockDim.x + threadIdx.x;
   const int seq = blockIdx.y;
@@ -533,25 +557,24 @@ __global__ __launch_bounds__(256) void score_merge_kernel(ScoreArgs a) {
   if (row >= a.lrows) return;
   const int split = row / (a.nb * 32);
   const int rb = (row - split * a.nb * 32) >> 5;
-  int chunk_base = 0;
-  for (int r = 0; r < seq; ++r)
-    chunk_base += (a.cu_seqlens[r + 1] - a.cu_seqlens[r] + a.chunk_keys - 1) / a.chunk_keys;
-  const int nch = (a.cu_seqlens[seq + 1] - a.cu_seqlens[seq] + a.chunk_keys - 1) / a.chunk_keys;
-  const int64_t chunk_stride = (int64_t)a.row_splits * a.srows * 2;
-  const float* st = a.stats + (((int64_t)lz * a.total_chunks + chunk_base) * a.row_splits + split) * a.srows * 2;
-  float M = NEG_BIG;
+  const int hi = lz * a.row_splits + split;
+  int tile_off = 0;
+  for (int r = 0; r < seq; ++r) tile_off += (a.cu_seqlens[r + 1] - a.cu_seqlens[r] + kTileKeys - 1) / kTileKeys;
+  const int nt = (a.cu_seqlens[seq + 1] - a.cu_seqlens[seq] + kTileKeys - 1) / kTileKeys;
+  const int x0 = hi * a.tiles_per_problem + tile_off;
+  const int g0 = wg_of_tile(x0, a.total_tiles, a.stat_wgs), g1 = wg_of_tile(x0 + nt - 1, a.total_tiles, a.stat_wgs);
+  const int p = hi * a.n_seqs + seq;
+  float M = NEG_BIG, L = 0.f;
   for (int h = 0; h < 2; ++h) {
     const int holder = a.rb_holder[rb][h];
     if (holder == 255) continue;
-    const float* sh = st + (holder * 32 + (row & 31)) * 2;
-    for (int ch = 0; ch < nch; ++ch) M = fmaxf(M, sh[ch * chunk_stride]);
-  }
-  float L = 0.f;
-  for (int h = 0; h < 2; ++h) {
-    const int holder = a.rb_holder[rb][h];
-    if (holder == 255) continue;
-    const float* sh = st + (holder * 32 + (row & 31)) * 2;
-    for (int ch = 0; ch < nch; ++ch) L += sh[ch * chunk_stride + 1] * __builtin_amdgcn_exp2f(sh[ch * chunk_stride] - M);
+    const float* sh = a.stats + ((int64_t)p * a.srows + holder * 32 + (row & 31)) * 2;
+    for (int g = g0; g <= g1; ++g) {
+      const float m = sh[(int64_t)g * a.srows * 2], l = sh[(int64_t)g * a.srows * 2 + 1];
+      const float Mn = fmaxf(M, m);
+      L = L * __builtin_amdgcn_exp2f(M - Mn) + l * __builtin_amdgcn_exp2f(m - Mn);
+      M = Mn;
+    }
   }
   a.lse[((int64_t)lz * a.n_seqs + seq) * a.lrows + row] = M + log2f(L);
 }
@@ -601,12 +624,39 @@ __global__ __launch_bounds__(256) void score_finish_kernel(FinishArgs a) {
   }
 }
 
+// Workgroups that run at once on the current device: compute units x resident workgroups per unit.
+template <class Kernel>
+static int resident_workgroups(Kernel kernel, int threads) {
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess) return 0;
+  return cus * per_cu;
+}
+
+// One launch "wave": as many workgroups as the device holds at once, each with an equal share of the
+// tiles (at least kMinTilesPerWorkgroup, so that small problems are not all prologue).
+static int score_grid(const Plan& pl, int resident) {
+  int g = resident > 0 ? resident : 256;
+  if (const char* e = getenv("CODECOMP_SCORE_WGS")) {        // experiments and tests: force the grid size
+    const int v = atoi(e);
+    if (v >= 1) g = v;
+  } else {
+    g = g < pl.total_tiles / kMinTilesPerWorkgroup ? g : pl.total_tiles / kMinTilesPerWorkgroup;
+  }
+  if (g > pl.total_tiles) g = pl.total_tiles;
+  if (g > kMaxScoreGrid) g = kMaxScoreGrid;
+  return g < 1 ? 1 : g;
+}
+
 template <int D, int NW>
-static int launch_passes(const Plan& pl, const ScoreArgs& a, hipStream_t stream, unsigned stages) {
-  const dim3 grid(pl.total_chunks, pl.row_splits, pl.L * pl.Hkv);
+static int launch_passes(const Plan& pl, ScoreArgs a, hipStream_t stream, unsigned stages) {
+  static const int resident1 = resident_workgroups(score_pass_kernel<D, NW, 1>, NW * 64);
+  static const int resident2 = resident_workgroups(score_pass_kernel<D, NW, 2>, NW * 64);
   const dim3 block(NW * 64);
+  a.stat_wgs = score_grid(pl, resident1);
   if (stages & CODECOMP_STAGE_ROW_STATS) {
-    score_pass_kernel<D, NW, 1><<<grid, block, 0, stream>>>(a);
+    score_pass_kernel<D, NW, 1><<<dim3(a.stat_wgs), block, 0, stream>>>(a);
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
   if (stages & CODECOMP_STAGE_ROW_MERGE) {
@@ -615,7 +665,7 @@ static int launch_passes(const Plan& pl, const ScoreArgs& a, hipStream_t stream,
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
   if (stages & CODECOMP_STAGE_MASS) {
-    score_pass_kernel<D, NW, 2><<<grid, block, 0, stream>>>(a);
+    score_pass_kernel<D, NW, 2><<<dim3(score_grid(pl, resident2)), block, 0, stream>>>(a);
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
   return 0;
@@ -648,7 +698,8 @@ int launch_score(const Plan& pl, const void* q, const void* k, const float* prio
   a.lrows = pl.row_splits * pl.row_blocks * 32;
   for (int w = 0; w < kMaxWaves; ++w) a.wave_desc[w] = pl.wave_desc[w];
   for (int b = 0; b < 2 * kMaxWaves; ++b) { a.rb_holder[b][0] = pl.rb_holder[b][0]; a.rb_holder[b][1] = pl.rb_holder[b][1]; }
-  a.chunk_keys = pl.chunk_keys; a.total_chunks = pl.total_chunks; a.T = pl.T;
+  a.tiles_per_problem = pl.tiles_per_problem; a.total_tiles = pl.total_tiles; a.stat_wgs = 0; a.T = pl.T;
+  a.LH = pl.L * pl.Hkv;
   a.q_sl = pl.q_sl; a.q_ss = pl.q_ss; a.q_sh = pl.q_sh; a.q_st = pl.q_st;
   a.kv_sl = pl.kv_sl; a.kv_sh = pl.kv_sh; a.kv_st = pl.kv_st;
   a.c = pl.scale * 1.4426950408889634f;
@@ -665,14 +716,14 @@ int launch_score(const Plan& pl, const void* q, const void* k, const float* prio
     hipMemcpyFromSymbol(simd_, HIP_SYMBOL(g_simd), sizeof(simd_));
     hipMemcpyFromSymbol(marks_, HIP_SYMBOL(g_marks), sizeof(marks_));
     if (FILE* f_ = fopen(path_, "w")) {
-      const int nwg_ = pl.total_chunks * pl.L * pl.Hkv;
+      const int nwg_ = 2048;
       for (int p_ = 0; p_ < 2; ++p_)
         for (int i_ = 0; i_ < nwg_ && i_ < 2048; ++i_)
-          fprintf(f_, "T %d %d %d %lld %lld %lld %u %u\n", p_ + 1, i_ % pl.total_chunks, i_ / pl.total_chunks, host_[p_][i_][0],
+          if (host_[p_][i_][1] != 0) fprintf(f_, "T %d %d %d %lld %lld %lld %u %u\n", p_ + 1, i_, 0, host_[p_][i_][0],
                   host_[p_][i_][1], host_[p_][i_][2], (unsigned)(host_[p_][i_][3] & 0xffffffff), (unsigned)(host_[p_][i_][3] >> 32));
       for (int p_ = 0; p_ < 2; ++p_)
         for (int i_ = 0; i_ < nwg_ && i_ < 2048; ++i_)
-          fprintf(f_, "M %d %lld %lld %lld %lld %lld %lld\n", p_ + 1, host_[p_][i_][0], marks_[p_][i_][0], marks_[p_][i_][1],
+          if (host_[p_][i_][1] != 0) fprintf(f_, "M %d %lld %lld %lld %lld %lld %lld\n", p_ + 1, host_[p_][i_][0], marks_[p_][i_][0], marks_[p_][i_][1],
                   marks_[p_][i_][2], marks_[p_][i_][3], host_[p_][i_][1]);
       for (int i_ = 0; i_ < 24; ++i_)
         fprintf(f_, "S %d : %d %d %d %d %d %d %d %d\n", i_ * 7, simd_[i_ * 7][0], simd_[i_ * 7][1], simd_[i_ * 7][2], simd_[i_ * 7][3],
