@@ -107,15 +107,22 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   int per = (pl->R + pl->row_splits - 1) / pl->row_splits;
   pl->row_blocks = (per + 31) / 32;
   assign_row_blocks(pl);
+  pl->lead_tiles = kLeadTiles;
+  if (const char* e = getenv("CODECOMP_SCORE_LEAD_TILES")) {   // tuning experiments
+    const int v = atoi(e);
+    if (v >= 0 && v <= 64) pl->lead_tiles = v;
+  }
   int64_t tiles = 0;
   for (int r = 0; r < p->n_seqs; ++r) {
     int n = p->cu_seqlens_host[r + 1] - p->cu_seqlens_host[r];
     tiles += (n + kTileKeys - 1) / kTileKeys;
   }
-  const int64_t total_tiles = tiles * pl->L * pl->Hkv * pl->row_splits;
-  if (total_tiles > (1 << 30)) return CODECOMP_EINVAL_SHAPE;
-  pl->tiles_per_problem = (int)tiles;
-  pl->total_tiles = (int)total_tiles;
+  const int64_t problems = (int64_t)pl->L * pl->Hkv * pl->row_splits;
+  const int64_t positions = tiles + (int64_t)pl->lead_tiles * pl->n_seqs;
+  if (positions * problems > (1 << 30)) return CODECOMP_EINVAL_SHAPE;
+  pl->tiles_per_problem = (int)positions;
+  pl->total_tiles = (int)(positions * problems);
+  pl->real_tiles = (int)(tiles * problems);
 
   const int64_t d = pl->d;
   pl->q_st = p->q_stride_tok ? p->q_stride_tok : d;

@@ -13,6 +13,7 @@ constexpr int kMaxWaves = 8;          // wavefronts per workgroup in the score k
 constexpr int kTileKeys = 64;         // keys staged through LDS per pipeline step
 constexpr int kMaxScoreGrid = 2048;   // most workgroups a score pass is launched with
 constexpr int kMinTilesPerWorkgroup = 4;
+constexpr int kLeadTiles = 4;         // a segment start (query fragments, first K tile) costs about this many tiles
 constexpr int kSelectThreads = 1024;  // one workgroup per (layer, head, request) in select
 
 struct Plan {
@@ -31,8 +32,10 @@ struct Plan {
   // ones slot 1 covers (0: the wave has no slot 1).
   uint32_t wave_desc[kMaxWaves];
   uint8_t rb_holder[2 * kMaxWaves][2];   // per row block: wave * 2 + slot of its (one or two) owners, 255 = none
-  int tiles_per_problem;     // sum over requests of ceil(N_r / kTileKeys): tiles of one (layer, head, row split)
+  int lead_tiles;            // empty positions before each request's tiles in the sequence below: the cost of starting a segment
+  int tiles_per_problem;     // sum over requests of (lead_tiles + ceil(N_r / kTileKeys)): positions of one (layer, head, row split)
   int total_tiles;           // L * Hkv * row_splits * tiles_per_problem, shared out evenly over the workgroups
+  int real_tiles;            // the same without the leads
   int64_t q_sl, q_ss, q_sh, q_st;
   int64_t kv_sl, kv_sh, kv_st;
   int64_t o_sl, o_sh, o_st;

@@ -40,10 +40,14 @@ struct ScoreArgs {
   float* uraw;    // [row_splits][L*Hkv][T]         : (1/G) * sum over this split's rows of A
   int n_seqs, Hkv, LH, G, W, R, row_splits, nb, srows, lrows, T;
   // Work distribution.  The 64-key tiles of all problems (layer*head, row split, request), in that order,
-  // form one sequence of total_tiles tiles; workgroup g of `wgs` takes tiles [g*total/wgs, (g+1)*total/wgs)
-  // and walks through the "segments" in which that range meets the problems.  Pass 1 leaves the statistics
-  // of the segment of workgroup g in problem p in slot g + p (distinct for distinct segments).
-  int tiles_per_problem;             // sum over requests of ceil(N_r / 64)
+  // form one sequence; workgroup g of `wgs` takes positions [g*total/wgs, (g+1)*total/wgs) and walks
+  // through the "segments" in which that range meets the problems.  Every problem is preceded by
+  // `lead` empty positions: starting a segment costs about that many tiles (query fragments, first K
+  // tile), so a range that crosses into a new problem gets that many tiles less, and all workgroups
+  // finish together.  Pass 1 leaves the statistics of the segment of workgroup g in problem p in slot
+  // g + p (distinct for distinct segments).
+  int lead;                          // empty positions before the tiles of each problem
+  int tiles_per_problem;             // sum over requests of (lead + ceil(N_r / 64))
   int total_tiles;                   // L*Hkv * row_splits * tiles_per_problem
   int stat_wgs;                      // workgroups of the pass-1 launch whose statistics `stats` holds
   uint32_t wave_desc[kMaxWaves];     // row block of slot 0 | row block of slot 1 << 8 | halves of slot 1 << 16 (bit 0: first, bit 1: second)
@@ -63,18 +67,18 @@ __device__ unsigned char g_simd[2048][8];     // SIMD id of each wave of a workg
 
 __device__ __forceinline__ bf16x8 frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// Request that holds tile `xr` of a problem's tile sequence.
-__device__ __forceinline__ void locate_tile(const int32_t* cu, int n_seqs, int xr, int& seq, int& tok0, int& n,
+// Request that holds position `xr` of a (layer*head, row split) sequence; tile_in_seq < 0 inside the lead.
+__device__ __forceinline__ void locate_tile(const int32_t* cu, int n_seqs, int lead, int xr, int& seq, int& tok0, int& n,
                                             int& tile_in_seq, int& tiles_of_seq) {
   int acc = 0;
   for (int r = 0; r < n_seqs; ++r) {
     const int a = cu[r], b = cu[r + 1];
     const int nt = (b - a + kTileKeys - 1) / kTileKeys;
-    if (xr < acc + nt || r == n_seqs - 1) {
-      seq = r; tok0 = a; n = b - a; tile_in_seq = xr - acc; tiles_of_seq = nt;
+    if (xr < acc + lead + nt || r == n_seqs - 1) {
+      seq = r; tok0 = a; n = b - a; tile_in_seq = xr - acc - lead; tiles_of_seq = nt;
       return;
     }
-    acc += nt;
+    acc += lead + nt;
   }
 }
 
@@ -133,13 +137,18 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   const int x_begin = (int)((int64_t)blockIdx.x * a.total_tiles / gridDim.x);
   const int x_end = (int)((int64_t)(blockIdx.x + 1) * a.total_tiles / gridDim.x);
   for (int x = x_begin; x < x_end;) {
-  const int hi = x / a.tiles_per_problem;                  // problem: (layer * Hkv + head) * row_splits + split
+  const int hi = x / a.tiles_per_problem;                  // (layer * Hkv + head) * row_splits + split
   const int lz = hi / a.row_splits;
   const int split = hi - lz * a.row_splits;
   const int layer = lz / a.Hkv;
   const int head = lz - layer * a.Hkv;
   int seq, tok0, n, tile_in_seq, tiles_of_seq;
-  locate_tile(a.cu_seqlens, a.n_seqs, x - hi * a.tiles_per_problem, seq, tok0, n, tile_in_seq, tiles_of_seq);
+  locate_tile(a.cu_seqlens, a.n_seqs, a.lead, x - hi * a.tiles_per_problem, seq, tok0, n, tile_in_seq, tiles_of_seq);
+  if (tile_in_seq < 0) {                                    // inside the lead: the problem's tiles start after it
+    x -= tile_in_seq;
+    tile_in_seq = 0;
+    if (x >= x_end) break;
+  }
   const int ntiles = min(x_end - x, tiles_of_seq - tile_in_seq);
   const int kstart = tile_in_seq * kTileKeys;
   const int kend = min(n, kstart + ntiles * kTileKeys);
@@ -173,36 +182,42 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   // ---- K tile staging: global -> registers -> LDS.  Rows past the end of the chunk re-read its
   // last key (always in bounds); such columns are masked (pass 1) or never stored (pass 2).
   const uint16_t* kb = a.k + (int64_t)layer * a.kv_sl + (int64_t)head * a.kv_sh + (int64_t)tok0 * a.kv_st;
+  // Workgroups that have a compute unit to themselves (more than four waves) keep two tiles in flight in two
+  // register sets in pass 2: with nothing else resident, a tile that arrives late stalls every SIMD of
+  // the unit.  (Measured: 4% off pass 2, nothing off pass 1, whose loop is the shorter one.)
+#ifdef CODECOMP_EXP_NO_DEEP
+  constexpr bool DEEP = false;
+#else
+  constexpr bool DEEP = NW > 4 && PASS == 2;
+#endif
   u32x4 stage[LD];
-  uint32_t soff[LD];                             // byte offset of this thread's i-th piece inside a tile
-#pragma unroll
-  for (int i = 0; i < LD; ++i) {
-    const int cidx = tid + i * NT;
-    const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;
-    soff[i] = (uint32_t)(row * (int)a.kv_st + col * 8) * 2u;
-  }
+  u32x4 stage2[DEEP ? LD : 1];
+  // byte offset of this thread's first 16-byte piece inside a tile; its i-th piece is NT / CH_PER_ROW rows further
+  static_assert(NT % CH_PER_ROW == 0, "pieces of one thread share a column");
+  const uint32_t soff0 = (uint32_t)((tid / CH_PER_ROW) * (int)a.kv_st + (tid % CH_PER_ROW) * 8) * 2u;
+  const uint32_t sstep = (uint32_t)((NT / CH_PER_ROW) * (int)a.kv_st) * 2u;
   // fast path: every staged row (slack rows included) lies inside the chunk -> uniform base + lane offset
-#define CODECOMP_GLOAD(KEY0)                                                                        \
+#define CODECOMP_GLOAD(KEY0, ST)                                                                    \
   {                                                                                                 \
     const int key0_ = (KEY0);                                                                       \
     if (key0_ + LDS_ROWS <= kend) {                                                                 \
       const char* tb_ = reinterpret_cast<const char*>(kb + (int64_t)key0_ * a.kv_st);               \
       _Pragma("unroll") for (int i = 0; i < LD; ++i)                                                \
-        stage[i] = *reinterpret_cast<const u32x4*>(tb_ + soff[i]);                                  \
+        ST[i] = *reinterpret_cast<const u32x4*>(tb_ + (size_t)i * sstep + soff0);                   \
     } else {                                                                                        \
       _Pragma("unroll") for (int i = 0; i < LD; ++i) {                                              \
         const int cidx = tid + i * NT;                                                              \
         const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;                           \
         const int key = min(key0_ + row, kend - 1);                                                 \
-        stage[i] = *reinterpret_cast<const u32x4*>(kb + (int64_t)key * a.kv_st + col * 8);          \
+        ST[i] = *reinterpret_cast<const u32x4*>(kb + (int64_t)key * a.kv_st + col * 8);             \
       }                                                                                             \
     }                                                                                               \
   }
-#define CODECOMP_SSTORE(BUF)                                                                        \
+#define CODECOMP_SSTORE(BUF, ST)                                                                    \
   _Pragma("unroll") for (int i = 0; i < LD; ++i) {                                                  \
     const int cidx = tid + i * NT;                                                                  \
     const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;                               \
-    *reinterpret_cast<u32x4*>(&ktile[BUF][row * ROWB + col * 16]) = stage[i];                       \
+    *reinterpret_cast<u32x4*>(&ktile[BUF][row * ROWB + col * 16]) = ST[i];                          \
   }
 
   const float c = a.c;
@@ -263,14 +278,17 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   auto lds_barrier = [&]() __attribute__((always_inline)) {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   };
-  // pass 1 only: logits of keys past the end of the chunk must not enter any row sum
+  // pass 1 only: logits of keys past the end of the segment must not enter any row sum.  A lane's 16
+  // logits of a sub-tile are keys in ascending order, so the valid ones are a prefix of length nvalid.
   auto mask_tail = [&](f32x16& x, int kh) __attribute__((always_inline)) {
     if constexpr (PASS == 1) {
+      // keys of this lane in sub-tile kh: kh*32 + 8*(v/4) + 4*hf + v%4; full groups of 8 keys below `rem`, then a part
+      const int left = rem - kh * 32 - 4 * hf;                       // keys at or after this lane's first one
+      const int part = left - 8 * (left >> 3);                       // 0..7
+      const int nvalid = left <= 0 ? 0 : 4 * (left >> 3) + (part < 4 ? part : 4);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key_local = kh * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-        if (key_local >= rem) x[v] = -INFINITY;
-      }
+      for (int v = 0; v < 16; ++v)
+        if (v >= nvalid) x[v] = -INFINITY;
     }
   };
 
@@ -375,21 +393,27 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   };
 
   // One tile = phase a + phase b.  A1 / B1: slot 1 computes sub-tile a / b.  MASKED (last, partial
-  // tile only) clears the logits of keys past the end of the chunk before they are consumed.
-  auto tile_body = [&](int t, auto masked, auto fast, auto a1, auto b1) __attribute__((always_inline)) {
+  // tile only) clears the logits of keys past the end of the segment before they are consumed.
+  // STG: which staging registers feed LDS in this tile: 0 = `stage`, next load two tiles ahead;
+  // 1 / 2 = `stage` / `stage2`, next load three tiles ahead (DEEP); 3 = none (last tile of a segment).
+  auto tile_body = [&](int t, auto masked, auto fast, auto a1, auto b1, auto stg) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked)::value;
+    constexpr int STG = decltype(stg)::value;
     constexpr bool FAST = PASS == 1 && decltype(fast)::value;
     constexpr bool A1 = decltype(a1)::value, B1 = decltype(b1)::value;
     const int buf = t & 1;
     const f32x16 zero = {0};
     // ---------------- phase a: logits of sub-tile a -> accA; softmax of accB (tile t-1, sub-tile b)
-    // tile t+1 waits in the staging registers: park it in the other LDS buffer (its last readers
-    // passed the previous barrier), then send the loads of tile t+2 on their way
+    // tile t+1 waits in staging registers: park it in the other LDS buffer (its last readers passed
+    // the previous barrier), then send the loads of a later tile on their way into the same registers
 #ifndef CODECOMP_EXP_NO_SSTORE
-    CODECOMP_SSTORE(buf ^ 1)
+    if constexpr (STG == 0 || STG == 1) { CODECOMP_SSTORE(buf ^ 1, stage) }
+    if constexpr (STG == 2) { CODECOMP_SSTORE(buf ^ 1, stage2) }
 #endif
 #ifndef CODECOMP_EXP_NO_GLOAD
-    CODECOMP_GLOAD(kstart + (t + 2) * kTileKeys)
+    if constexpr (STG == 0) CODECOMP_GLOAD(kstart + (t + 2) * kTileKeys, stage)
+    if constexpr (STG == 1) CODECOMP_GLOAD(kstart + (t + 3) * kTileKeys, stage)
+    if constexpr (STG == 2) CODECOMP_GLOAD(kstart + (t + 3) * kTileKeys, stage2)
 #endif
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -441,9 +465,10 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 #pragma unroll
     for (int v = 0; v < 16; ++v) { accB0[v] = -INFINITY; accB1[v] = -INFINITY; }
     m_run0 = NEG_BIG; m_run1 = NEG_BIG; l_run0 = 0.f; l_run1 = 0.f; mc0 = 0.f; mc1 = 0.f;
-    CODECOMP_GLOAD(kstart)
-    CODECOMP_SSTORE(0)
-    CODECOMP_GLOAD(kstart + kTileKeys)
+    CODECOMP_GLOAD(kstart, stage)
+    CODECOMP_SSTORE(0, stage)
+    CODECOMP_GLOAD(kstart + kTileKeys, stage)
+    if constexpr (DEEP) CODECOMP_GLOAD(kstart + 2 * kTileKeys, stage2)
     lds_barrier();
 #if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
     mark_[1] = __builtin_amdgcn_s_memrealtime();
@@ -451,16 +476,32 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 #pragma unroll
     for (int r = 0; r < RING; ++r) ring[r] = *kfrag_ptr(0, 0, r);
 
+    using stg = std::integral_constant<int, 0>;
+    using stg_even = std::integral_constant<int, 1>;
+    using stg_odd = std::integral_constant<int, 2>;
+    using stg_none = std::integral_constant<int, 3>;
     const int nplain = rem != 0 ? ntiles - 1 : ntiles;
-    for (int t = 0; t < nplain; ++t) {
-#ifndef CODECOMP_EXP_NO_REDUCE
-      reduce_cols(t - 2);
-#endif
-      tile_body(t, std::false_type{}, fast, a1, b1);
+    if constexpr (DEEP) {
+      int t = 0;
+      for (; t + 1 < nplain; t += 2) {           // even tiles are fed from `stage`, odd ones from `stage2`
+        reduce_cols(t - 2);
+        tile_body(t, std::false_type{}, fast, a1, b1, stg_even{});
+        reduce_cols(t - 1);
+        tile_body(t + 1, std::false_type{}, fast, a1, b1, stg_odd{});
+      }
+      if (t < nplain) {
+        reduce_cols(t - 2);
+        tile_body(t, std::false_type{}, fast, a1, b1, stg_even{});
+      }
+    } else {
+      for (int t = 0; t < nplain; ++t) {
+        reduce_cols(t - 2);
+        tile_body(t, std::false_type{}, fast, a1, b1, stg{});
+      }
     }
     if (rem != 0) {
       reduce_cols(ntiles - 3);
-      tile_body(ntiles - 1, std::true_type{}, fast, a1, b1);
+      tile_body(ntiles - 1, std::true_type{}, fast, a1, b1, stg_none{});
     }
 #if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
     mark_[2] = __builtin_amdgcn_s_memrealtime();
@@ -558,8 +599,8 @@ __global__ __launch_bounds__(256) void score_merge_kernel(ScoreArgs a) {
   const int split = row / (a.nb * 32);
   const int rb = (row - split * a.nb * 32) >> 5;
   const int hi = lz * a.row_splits + split;
-  int tile_off = 0;
-  for (int r = 0; r < seq; ++r) tile_off += (a.cu_seqlens[r + 1] - a.cu_seqlens[r] + kTileKeys - 1) / kTileKeys;
+  int tile_off = a.lead;
+  for (int r = 0; r < seq; ++r) tile_off += a.lead + (a.cu_seqlens[r + 1] - a.cu_seqlens[r] + kTileKeys - 1) / kTileKeys;
   const int nt = (a.cu_seqlens[seq + 1] - a.cu_seqlens[seq] + kTileKeys - 1) / kTileKeys;
   const int x0 = hi * a.tiles_per_problem + tile_off;
   const int g0 = wg_of_tile(x0, a.total_tiles, a.stat_wgs), g1 = wg_of_tile(x0 + nt - 1, a.total_tiles, a.stat_wgs);
@@ -642,9 +683,9 @@ static int score_grid(const Plan& pl, int resident) {
     const int v = atoi(e);
     if (v >= 1) g = v;
   } else {
-    g = g < pl.total_tiles / kMinTilesPerWorkgroup ? g : pl.total_tiles / kMinTilesPerWorkgroup;
+    g = g < pl.real_tiles / kMinTilesPerWorkgroup ? g : pl.real_tiles / kMinTilesPerWorkgroup;
   }
-  if (g > pl.total_tiles) g = pl.total_tiles;
+  if (g > pl.real_tiles) g = pl.real_tiles;
   if (g > kMaxScoreGrid) g = kMaxScoreGrid;
   return g < 1 ? 1 : g;
 }
@@ -698,7 +739,7 @@ int launch_score(const Plan& pl, const void* q, const void* k, const float* prio
   a.lrows = pl.row_splits * pl.row_blocks * 32;
   for (int w = 0; w < kMaxWaves; ++w) a.wave_desc[w] = pl.wave_desc[w];
   for (int b = 0; b < 2 * kMaxWaves; ++b) { a.rb_holder[b][0] = pl.rb_holder[b][0]; a.rb_holder[b][1] = pl.rb_holder[b][1]; }
-  a.tiles_per_problem = pl.tiles_per_problem; a.total_tiles = pl.total_tiles; a.stat_wgs = 0; a.T = pl.T;
+  a.lead = pl.lead_tiles; a.tiles_per_problem = pl.tiles_per_problem; a.total_tiles = pl.total_tiles; a.stat_wgs = 0; a.T = pl.T;
   a.LH = pl.L * pl.Hkv;
   a.q_sl = pl.q_sl; a.q_ss = pl.q_ss; a.q_sh = pl.q_sh; a.q_st = pl.q_st;
   a.kv_sl = pl.kv_sl; a.kv_sh = pl.kv_sh; a.kv_st = pl.kv_st;

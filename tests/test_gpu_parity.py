@@ -76,6 +76,37 @@ def test_ragged_batch():
     run_case(w, fused=False)
 
 
+@pytest.mark.parametrize("wgs,lead", [(1, 4), (3, 0), (7, 4), (13, 9), (64, 1), (2048, 4), (2048, 40)])
+def test_any_split_of_the_tile_sequence_gives_the_same_scores(wgs, lead, monkeypatch):
+    """The score passes cut the tile sequence of all (layer, head, request) problems into one range per
+    workgroup; a range may cover several problems, start inside one, or hold no tile at all.  Forced grid
+    sizes and segment-start weights: the result must not depend on them (fp32 sums regroup: 1e-5)."""
+    import torch
+    b = _binding()
+    w = wl.scaled(wl.ragged_agentic(), n_layers=2, seqlens=[700, 1300, 64, 2049, 130], budgets=[70, 130, 64, 204, 70])
+    q, k, v, prior = wl.make_all(w)
+    ref = b.DeviceProblem(w, q, k, v, prior)
+    ref.score()
+    torch.cuda.synchronize()
+    sc_ref = ref.scores.cpu().numpy()
+    cu = w.cu_seqlens()
+    pu.assert_scores_close(sc_ref, orc.score_packed(q, k, prior, cu, pool_kernel=w.pool_kernel, prior_weight=w.prior_weight))
+    monkeypatch.setenv("CODECOMP_SCORE_WGS", str(wgs))
+    monkeypatch.setenv("CODECOMP_SCORE_LEAD_TILES", str(lead))
+    prob = b.DeviceProblem(w, q, k, v, prior)
+    prob.score()
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(prob.scores.cpu().numpy(), sc_ref, rtol=1e-5, atol=1e-30)
+
+
+@pytest.mark.parametrize("group,window", [(5, 64), (6, 64), (7, 64), (3, 100), (9, 32), (13, 40), (15, 32), (16, 32)])
+def test_row_blocks_shared_between_waves(group, window):
+    """More than 8 blocks of 32 softmax rows: eight waves, some blocks owned by two waves (one per half of
+    every tile); their statistics are merged per row."""
+    run_case(wl.scaled(wl.qwen7b_32k(), n_layers=1, seqlens=[1500, 230], budgets=[window + 50, window + 3], window=window,
+                       n_q_heads=2 * group, n_kv_heads=2))
+
+
 @pytest.mark.parametrize("kw", [
     dict(seqlens=[32], budgets=[32], window=32),                       # N == W == B: window only, no prefix
     dict(seqlens=[1], budgets=[1], window=1),                          # a single token
