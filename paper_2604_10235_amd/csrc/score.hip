@@ -126,6 +126,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 #endif
 #if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
   long long mark_[4] = {0, 0, 0, 0};
+
   int nseg_ = 0;
 #endif
   // ---- what this wave owns (the same for every lane: keep it in scalar registers)
@@ -197,9 +198,14 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   const uint32_t soff0 = (uint32_t)((tid / CH_PER_ROW) * (int)a.kv_st + (tid % CH_PER_ROW) * 8) * 2u;
   const uint32_t sstep = (uint32_t)((NT / CH_PER_ROW) * (int)a.kv_st) * 2u;
   // fast path: every staged row (slack rows included) lies inside the chunk -> uniform base + lane offset
+#ifdef CODECOMP_EXP_NEAR_GLOAD   /* experiment: always re-read the first tile of the segment (cache hits) */
+#define CODECOMP_KEY0(X) (((X) & 0) + kstart)
+#else
+#define CODECOMP_KEY0(X) (X)
+#endif
 #define CODECOMP_GLOAD(KEY0, ST)                                                                    \
   {                                                                                                 \
-    const int key0_ = (KEY0);                                                                       \
+    const int key0_ = CODECOMP_KEY0(KEY0);                                                          \
     if (key0_ + LDS_ROWS <= kend) {                                                                 \
       const char* tb_ = reinterpret_cast<const char*>(kb + (int64_t)key0_ * a.kv_st);               \
       _Pragma("unroll") for (int i = 0; i < LD; ++i)                                                \
@@ -571,6 +577,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     const int idx_ = blockIdx.x;
     if (idx_ < 2048) {
       for (int q_ = 0; q_ < 4; ++q_) g_marks[PASS - 1][idx_][q_] = mark_[q_];
+
       g_trace[PASS - 1][idx_][0] = rt0_;
       g_trace[PASS - 1][idx_][1] = __builtin_amdgcn_s_memrealtime();
       g_trace[PASS - 1][idx_][2] = __builtin_readcyclecounter() - clk0_;
@@ -586,6 +593,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 #endif
 #endif
 #undef CODECOMP_GLOAD
+#undef CODECOMP_KEY0
 #undef CODECOMP_SSTORE
 }
 
