@@ -35,6 +35,16 @@ Readings where the paper is silent (all listed again in the design notes of this
   - ties between equal scores go to the lower token index;
   - kept indices are emitted in ascending order.
 
+Variants of the score tail (other readings of what the paper leaves open, switchable; the
+defaults are the readings above):
+  - group_reduce "sum" / "max": the G query heads of a KV head are summed / the largest head
+    mass wins, instead of averaged;
+  - pool_mode "max": max pooling instead of the appendix's average pooling;
+  - softmax_domain "prefix": the softmax of section "Attention-based KV Cache Compression"
+    runs over the context keys only (its K "in R^{L_c x d}"), i.e. the N - W keys before the
+    observation window; window columns get no mass;
+  - pool_domain "prefix": pooling never looks across the boundary between context and window.
+
 All arrays are numpy.  bf16 inputs arrive as uint16 bit patterns and are widened exactly.
 """
 from __future__ import annotations
@@ -61,30 +71,39 @@ def attention_rows(q: np.ndarray, k: np.ndarray, scale: float) -> np.ndarray:
     return e / e.sum(axis=1, keepdims=True)
 
 
-def window_attention_mass(q_obs: np.ndarray, k: np.ndarray, scale: float | None = None) -> np.ndarray:
-    """u[h, j] = (1/G) sum_{g<G} sum_{t<W} A[h*G+g][t, j].
+def window_attention_mass(q_obs: np.ndarray, k: np.ndarray, scale: float | None = None, *,
+                          group_reduce: str = "mean", softmax_keys: int | None = None) -> np.ndarray:
+    """u[h, j] = reduce_{g<G} sum_{t<W} A[h*G+g][t, j], reduce = mean (default), sum or max.
 
     q_obs float64 [H_q, W, d]; k float64 [H_kv, N, d]; returns float64 [H_kv, N].
-    Query head h_q reads KV head h_q // G (contiguous grouping)."""
+    Query head h_q reads KV head h_q // G (contiguous grouping).  softmax_keys = m restricts
+    every softmax to the first m keys; the other columns get zero mass."""
     h_q, w, d = q_obs.shape
     h_kv, n, d2 = k.shape
-    assert d == d2 and h_q % h_kv == 0
+    assert d == d2 and h_q % h_kv == 0 and group_reduce in ("mean", "sum", "max")
     g = h_q // h_kv
+    m = n if softmax_keys is None else int(softmax_keys)
+    assert 0 <= m <= n
     if scale is None:
         scale = 1.0 / np.sqrt(d)
-    u = np.zeros((h_kv, n), dtype=np.float64)
-    for hq in range(h_q):
-        a = attention_rows(q_obs[hq], k[hq // g], scale)
-        u[hq // g] += a.sum(axis=0)               # u(j) = sum_t A(t, j)
-    return u / g
+    per_head = np.zeros((h_q, n), dtype=np.float64)
+    if m > 0:
+        for hq in range(h_q):
+            a = attention_rows(q_obs[hq], k[hq // g, :m], scale)
+            per_head[hq, :m] = a.sum(axis=0)      # u(j) = sum_t A(t, j)
+    grouped = per_head.reshape(h_kv, g, n)
+    if group_reduce == "max":
+        return grouped.max(axis=1)
+    u = grouped.sum(axis=1)
+    return u / g if group_reduce == "mean" else u
 
 
-def average_pool(u: np.ndarray, kernel: int) -> np.ndarray:
-    """pooled[j] = (1/k) sum_{|delta| <= (k-1)/2} u[j + delta], terms outside [0, N) are zero.
-    Works on the last axis."""
+def average_pool(u: np.ndarray, kernel: int, extent: int | None = None) -> np.ndarray:
+    """pooled[j] = (1/k) sum_{|delta| <= (k-1)/2} u[j + delta], terms outside [0, E) are zero.
+    Works on the last axis.  E = extent (default: the whole axis); positions >= E get 0."""
     assert kernel >= 1 and kernel % 2 == 1
     half = (kernel - 1) // 2
-    n = u.shape[-1]
+    n = u.shape[-1] if extent is None else int(extent)
     out = np.zeros_like(u, dtype=np.float64)
     for delta in range(-half, half + 1):
         lo, hi = max(0, -delta), min(n, n - delta)        # j with 0 <= j + delta < n
@@ -93,16 +112,34 @@ def average_pool(u: np.ndarray, kernel: int) -> np.ndarray:
     return out / kernel
 
 
+def max_pool(u: np.ndarray, kernel: int, extent: int | None = None) -> np.ndarray:
+    """pooled[j] = max_{|delta| <= (k-1)/2, 0 <= j + delta < E} u[j + delta]; positions >= E get 0."""
+    assert kernel >= 1 and kernel % 2 == 1
+    half = (kernel - 1) // 2
+    n = u.shape[-1] if extent is None else int(extent)
+    out = np.zeros_like(u, dtype=np.float64)
+    for j in range(n):
+        out[..., j] = u[..., max(0, j - half):min(n, j + half + 1)].max(axis=-1)
+    return out
+
+
 def fuse_prior(pooled: np.ndarray, prior: np.ndarray, prior_weight: float) -> np.ndarray:
     """c[h, j] = pooled[h, j] + lambda * p[j]; the prior is shared by all heads."""
     return pooled + float(prior_weight) * np.asarray(prior, dtype=np.float64)[None, :]
 
 
 def score(q_obs: np.ndarray, k: np.ndarray, prior: np.ndarray, *, pool_kernel: int,
-          prior_weight: float, scale: float | None = None) -> np.ndarray:
-    """Scores of one request in one layer: float64 [H_kv, N]."""
-    u = window_attention_mass(q_obs, k, scale)
-    return fuse_prior(average_pool(u, pool_kernel), prior, prior_weight)
+          prior_weight: float, scale: float | None = None, group_reduce: str = "mean",
+          pool_mode: str = "avg", softmax_domain: str = "all", pool_domain: str = "row") -> np.ndarray:
+    """Scores of one request in one layer: float64 [H_kv, N].  The observation window is the
+    last W = q_obs.shape[1] tokens; "prefix" domains are the N - W tokens before it."""
+    assert pool_mode in ("avg", "max") and softmax_domain in ("all", "prefix") and pool_domain in ("row", "prefix")
+    n, w = k.shape[1], q_obs.shape[1]
+    u = window_attention_mass(q_obs, k, scale, group_reduce=group_reduce,
+                              softmax_keys=n - w if softmax_domain == "prefix" else None)
+    extent = n - w if pool_domain == "prefix" else None
+    pooled = average_pool(u, pool_kernel, extent) if pool_mode == "avg" else max_pool(u, pool_kernel, extent)
+    return fuse_prior(pooled, prior, prior_weight)
 
 
 # ----------------------------------------------------------------------------------------
@@ -144,7 +181,7 @@ def gather(k: np.ndarray, v: np.ndarray, idx: np.ndarray):
 # ----------------------------------------------------------------------------------------
 
 def score_packed(q_bits, k_bits, prior, cu_seqlens, *, pool_kernel, prior_weight, scale=None,
-                 layers=None) -> np.ndarray:
+                 layers=None, **variant) -> np.ndarray:
     """q_bits uint16 [L][n_seqs][H_q][W][d], k_bits uint16 [L][H_kv][T][d], prior [T],
     cu_seqlens [n_seqs+1] -> scores float64 [L][H_kv][T].  Every (layer, request) is scored
     on its own; layers not listed in `layers` are left as NaN."""
@@ -154,7 +191,8 @@ def score_packed(q_bits, k_bits, prior, cu_seqlens, *, pool_kernel, prior_weight
         for r in range(len(cu_seqlens) - 1):
             a, b = int(cu_seqlens[r]), int(cu_seqlens[r + 1])
             out[l, :, a:b] = score(bf16_bits_to_f64(q_bits[l, r]), bf16_bits_to_f64(k_bits[l, :, a:b]),
-                                   prior[a:b], pool_kernel=pool_kernel, prior_weight=prior_weight, scale=scale)
+                                   prior[a:b], pool_kernel=pool_kernel, prior_weight=prior_weight, scale=scale,
+                                   **variant)
     return out
 
 

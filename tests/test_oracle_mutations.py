@@ -55,12 +55,12 @@ def _mass(q_obs, k, scale, *, group_sum=False, softmax_axis=1, interleaved_heads
 
 
 MASS_MUTANTS = {
-    "scale 1/d": lambda q, k, scale=None: _mass(q, k, 1.0 / q.shape[-1]),
-    "no scale": lambda q, k, scale=None: _mass(q, k, 1.0),
-    "sum over the group": lambda q, k, scale=None: _mass(q, k, 1 / math.sqrt(q.shape[-1]), group_sum=True),
-    "softmax over queries": lambda q, k, scale=None: _mass(q, k, 1 / math.sqrt(q.shape[-1]), softmax_axis=0),
-    "interleaved head mapping": lambda q, k, scale=None: _mass(q, k, 1 / math.sqrt(q.shape[-1]), interleaved_heads=True),
-    "negated logits": lambda q, k, scale=None: _mass(q, k, 1 / math.sqrt(q.shape[-1]), transpose=True),
+    "scale 1/d": lambda q, k, scale=None, **kw: _mass(q, k, 1.0 / q.shape[-1]),
+    "no scale": lambda q, k, scale=None, **kw: _mass(q, k, 1.0),
+    "sum over the group": lambda q, k, scale=None, **kw: _mass(q, k, 1 / math.sqrt(q.shape[-1]), group_sum=True),
+    "softmax over queries": lambda q, k, scale=None, **kw: _mass(q, k, 1 / math.sqrt(q.shape[-1]), softmax_axis=0),
+    "interleaved head mapping": lambda q, k, scale=None, **kw: _mass(q, k, 1 / math.sqrt(q.shape[-1]), interleaved_heads=True),
+    "negated logits": lambda q, k, scale=None, **kw: _mass(q, k, 1 / math.sqrt(q.shape[-1]), transpose=True),
 }
 
 
@@ -86,9 +86,9 @@ def _pool(u, kernel, *, divisor="k", shift=0):
 
 
 POOL_MUTANTS = {
-    "divide by the covered count": lambda u, k: _pool(u, k, divisor="count"),
-    "window shifted by one": lambda u, k: _pool(u, k, shift=1),
-    "no pooling": lambda u, k: u.astype(np.float64),
+    "divide by the covered count": lambda u, k, extent=None: _pool(u, k, divisor="count"),
+    "window shifted by one": lambda u, k, extent=None: _pool(u, k, shift=1),
+    "no pooling": lambda u, k, extent=None: u.astype(np.float64),
 }
 
 

@@ -428,3 +428,85 @@ def test_two_stage_invariants_and_optimality():
             assert set(best) <= chosen
             rest = sorted(set(range(npre)) - set(best), key=lambda j: (-pooled[hh, j], j))[: bp - npro]
             assert chosen == set(best) | set(rest)
+
+
+# ----------------------------------------------------------------------------------------
+# variants of the score tail
+# ----------------------------------------------------------------------------------------
+
+def _rand_case(seed, h_q=6, h_kv=2, w=3, n=23, d=8):
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((h_q, w, d)), rng.standard_normal((h_kv, n, d)), rng.random(n)
+
+
+def test_group_sum_is_g_times_mean_and_max_is_the_largest_head():
+    q, k, _ = _rand_case(1)
+    mean = orc.window_attention_mass(q, k)
+    np.testing.assert_allclose(orc.window_attention_mass(q, k, group_reduce="sum"), 3 * mean, rtol=1e-13)
+    # per-head masses from single-head calls (G = 1 on a repeated KV head), then max by hand
+    heads = np.stack([orc.window_attention_mass(q[h:h + 1], k[h // 3:h // 3 + 1])[0] for h in range(6)])
+    np.testing.assert_allclose(orc.window_attention_mass(q, k, group_reduce="max"),
+                               np.stack([heads[:3].max(axis=0), heads[3:].max(axis=0)]), rtol=1e-13)
+    # identical query heads: mean == max, sum == G * max
+    qq = np.repeat(q[:2], 3, axis=0)[[0, 1, 2, 3, 4, 5]]
+    qq[0:3] = q[0]; qq[3:6] = q[1]
+    np.testing.assert_allclose(orc.window_attention_mass(qq, k, group_reduce="max"), orc.window_attention_mass(qq, k), rtol=1e-13)
+
+
+def test_prefix_softmax_is_the_full_softmax_on_truncated_keys():
+    q, k, _ = _rand_case(2)
+    n, w = k.shape[1], q.shape[1]
+    u = orc.window_attention_mass(q, k, softmax_keys=n - w)
+    np.testing.assert_allclose(u[:, :n - w], orc.window_attention_mass(q, k[:, :n - w]), rtol=1e-13)
+    assert (u[:, n - w:] == 0).all()
+    np.testing.assert_allclose(u.sum(axis=1), w, rtol=1e-12)          # all the mass sits on the prefix
+    # uniform keys: W / (N - W) on the prefix
+    uz = orc.window_attention_mass(q, np.zeros_like(k), softmax_keys=n - w)
+    np.testing.assert_allclose(uz[:, :n - w], w / (n - w), rtol=1e-13)
+    # through score(): same thing with lambda = 0 and no pooling
+    sc = orc.score(q, k, np.zeros(n), pool_kernel=1, prior_weight=0.0, softmax_domain="prefix")
+    np.testing.assert_allclose(sc, u, rtol=1e-13)
+    # no prefix at all: nothing to attend to, all zero
+    assert (orc.window_attention_mass(q, k[:, :w], softmax_keys=0) == 0).all()
+
+
+@pytest.mark.parametrize("kernel,n", [(1, 9), (3, 10), (5, 17), (7, 7), (9, 4)])
+def test_max_pool_matches_library_max_pool(kernel, n):
+    rng = np.random.default_rng(kernel * 100 + n)
+    u = rng.random((3, n))                       # masses are non-negative
+    ref = torch.nn.functional.max_pool1d(torch.from_numpy(u)[None], kernel, stride=1, padding=(kernel - 1) // 2)[0].numpy()
+    np.testing.assert_array_equal(orc.max_pool(u, kernel), ref)
+    # monotone signal: the window maximum is the value (k-1)/2 places further on
+    ramp = np.arange(n, dtype=np.float64)[None]
+    np.testing.assert_array_equal(orc.max_pool(ramp, kernel)[0], np.minimum(np.arange(n) + (kernel - 1) // 2, n - 1))
+
+
+@pytest.mark.parametrize("mode", ["avg", "max"])
+def test_prefix_pooling_is_pooling_of_the_prefix_slice(mode):
+    rng = np.random.default_rng(7)
+    u = rng.random((2, 31))
+    pool = orc.average_pool if mode == "avg" else orc.max_pool
+    for kernel, extent in [(5, 20), (7, 31), (3, 1), (9, 0)]:
+        out = pool(u, kernel, extent)
+        np.testing.assert_array_equal(out[:, :extent], pool(u[:, :extent], kernel))
+        assert (out[:, extent:] == 0).all()
+    # library pin for the average on the slice
+    ref = torch.nn.functional.avg_pool1d(torch.from_numpy(u[:, :20])[None], 5, stride=1, padding=2, count_include_pad=True)[0].numpy()
+    np.testing.assert_allclose(orc.average_pool(u, 5, 20)[:, :20], ref, rtol=1e-14)
+
+
+def test_score_variants_compose_and_default_is_unchanged():
+    q, k, p = _rand_case(3)
+    n, w = k.shape[1], q.shape[1]
+    base = orc.score(q, k, p, pool_kernel=5, prior_weight=0.7)
+    np.testing.assert_array_equal(base, orc.score(q, k, p, pool_kernel=5, prior_weight=0.7, group_reduce="mean",
+                                                  pool_mode="avg", softmax_domain="all", pool_domain="row"))
+    full = orc.score(q, k, p, pool_kernel=5, prior_weight=0.7, group_reduce="sum", pool_mode="max",
+                     softmax_domain="prefix", pool_domain="prefix")
+    by_hand = orc.max_pool(3 * orc.window_attention_mass(q, k[:, :n - w]), 5)
+    np.testing.assert_allclose(full[:, :n - w], by_hand + 0.7 * p[None, :n - w], rtol=1e-13)
+    np.testing.assert_allclose(full[:, n - w:], np.broadcast_to(0.7 * p[None, n - w:], (2, w)), rtol=1e-13)
+    # selection at lambda = 0 does not care about mean vs sum (a positive factor)
+    a = orc.select(orc.score(q, k, p, pool_kernel=3, prior_weight=0.0), w, 9)
+    b_ = orc.select(orc.score(q, k, p, pool_kernel=3, prior_weight=0.0, group_reduce="sum"), w, 9)
+    np.testing.assert_array_equal(a, b_)
