@@ -58,7 +58,7 @@ enum {
   CODECOMP_EINVAL_SEQLENS = -8,   /* cu_seqlens / cu_budgets not starting at 0 or not increasing  */
   CODECOMP_EINVAL_WORKSPACE = -9, /* workspace NULL, misaligned (256 B) or too small              */
   CODECOMP_EINVAL_PRIOR = -10,    /* prior_weight negative or not finite; softmax_scale < 0       */
-  CODECOMP_EINVAL_MODE = -11      /* select_mode unknown, wrong for the call, or bad span budget  */
+  CODECOMP_EINVAL_MODE = -11      /* select_mode / score_variant unknown or unsupported for the shape, bad span budget */
 };
 
 typedef struct codecomp_params {
@@ -84,7 +84,27 @@ typedef struct codecomp_params {
    * floor(span_budget_ratio * Bp))) with Bp = B_r - W; the paper uses a ratio of 0.5 */
   float span_budget_ratio;     /* rho_span in [0, 1]                                              */
   int32_t span_budget_min;     /* B_min >= 0                                                      */
+  int32_t score_variant;       /* bit flags CODECOMP_VARIANT_*; 0 = the default readings          */
+  int32_t reserved;            /* must be 0                                                       */
 } codecomp_params;
+
+/* Other readings of what the paper leaves open about the tail of the score step (section
+ * "Attention-based KV Cache Compression" and appendix "Compression settings"), for comparison with the
+ * defaults (mean over the query-head group, average pooling, softmax and pooling over the whole request):
+ *   GROUP_SUM      the masses of the G query heads of a KV head are summed, not averaged;
+ *   GROUP_MAX      the largest head mass wins (needs window % 32 == 0 and G * window <= 512);
+ *   POOL_MAX       max pooling over the pool_kernel neighbours instead of their average;
+ *   SOFTMAX_PREFIX the softmax runs over the N - W context keys only (the K "in R^{L_c x d}" of the
+ *                  section); window positions get no attention mass;
+ *   POOL_PREFIX    pooling stays inside the N - W context positions; window positions get none.
+ * GROUP_SUM and GROUP_MAX exclude each other.  Unknown bits are rejected (CODECOMP_EINVAL_MODE). */
+enum {
+  CODECOMP_VARIANT_GROUP_SUM = 1,
+  CODECOMP_VARIANT_GROUP_MAX = 2,
+  CODECOMP_VARIANT_POOL_MAX = 4,
+  CODECOMP_VARIANT_SOFTMAX_PREFIX = 8,
+  CODECOMP_VARIANT_POOL_PREFIX = 16
+};
 
 /* How the structural prior enters the selection.
  * ADDITIVE : scores = pooled attention + lambda * prior, one top-(B - W) over them.

@@ -37,6 +37,7 @@ class codecomp_params(C.Structure):
         ("kv_stride_layer", C.c_int64), ("kv_stride_head", C.c_int64), ("kv_stride_tok", C.c_int64),
         ("out_stride_layer", C.c_int64), ("out_stride_head", C.c_int64), ("out_stride_tok", C.c_int64),
         ("span_budget_ratio", C.c_float), ("span_budget_min", C.c_int32),
+        ("score_variant", C.c_int32), ("reserved", C.c_int32),
     ]
 
 
@@ -161,6 +162,7 @@ def codecomp_score(q_obs, k, prior, params, scores, workspace) -> None:
 
 
 STAGE_ROW_STATS, STAGE_ROW_MERGE, STAGE_MASS, STAGE_FINISH, STAGE_ALL = 1, 2, 4, 8, 15
+VARIANT_GROUP_SUM, VARIANT_GROUP_MAX, VARIANT_POOL_MAX, VARIANT_SOFTMAX_PREFIX, VARIANT_POOL_PREFIX = 1, 2, 4, 8, 16
 
 
 def codecomp_score_stages(q_obs, k, prior, params, scores, workspace, stages: int) -> None:
@@ -226,7 +228,7 @@ class DeviceProblem:
 
     def __init__(self, w, q_bits: np.ndarray, k_bits: np.ndarray, v_bits: Optional[np.ndarray], prior: np.ndarray,
                  device: str = "cuda:0", select_mode: int = 0, span_budget_ratio: float = 0.5,
-                 span_budget_min: int = 0):
+                 span_budget_min: int = 0, score_variant: int = 0):
         import torch
         self.w = w
         dev = torch.device(device)
@@ -246,7 +248,8 @@ class DeviceProblem:
                                   prior_weight=w.prior_weight, cu_seqlens_host=w.cu_seqlens(),
                                   cu_budgets_host=w.cu_budgets(), cu_seqlens_dev=_ptr(self.cu_seqlens),
                                   cu_budgets_dev=_ptr(self.cu_budgets), select_mode=select_mode,
-                                  span_budget_ratio=span_budget_ratio, span_budget_min=span_budget_min)
+                                  span_budget_ratio=span_budget_ratio, span_budget_min=span_budget_min,
+                                  score_variant=score_variant)
         rc = codecomp_validate(self.params)
         _check(rc, "codecomp_validate")
         T, TB = w.total_tokens, w.total_budget

@@ -64,6 +64,10 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   if (p->select_mode == CODECOMP_SELECT_TWO_STAGE &&
       (!(p->span_budget_ratio >= 0.0f) || !(p->span_budget_ratio <= 1.0f) || p->span_budget_min < 0))
     return CODECOMP_EINVAL_MODE;
+  constexpr int kKnownVariants = CODECOMP_VARIANT_GROUP_SUM | CODECOMP_VARIANT_GROUP_MAX | CODECOMP_VARIANT_POOL_MAX |
+                                 CODECOMP_VARIANT_SOFTMAX_PREFIX | CODECOMP_VARIANT_POOL_PREFIX;
+  if ((p->score_variant & ~kKnownVariants) != 0 || p->reserved != 0) return CODECOMP_EINVAL_MODE;
+  if ((p->score_variant & CODECOMP_VARIANT_GROUP_SUM) && (p->score_variant & CODECOMP_VARIANT_GROUP_MAX)) return CODECOMP_EINVAL_MODE;
   if ((int64_t)p->n_layers * p->n_kv_heads > 65535) return CODECOMP_EINVAL_SHAPE;   // one grid axis
   if (p->n_kv_heads < 1 || p->n_q_heads < 1 || p->n_q_heads % p->n_kv_heads != 0) return CODECOMP_EINVAL_HEADS;
   if (p->head_dim != 64 && p->head_dim != 128) return CODECOMP_EINVAL_HEADDIM;
@@ -92,6 +96,8 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   pl->L = p->n_layers; pl->Hq = p->n_q_heads; pl->Hkv = p->n_kv_heads; pl->G = pl->Hq / pl->Hkv;
   pl->d = p->head_dim; pl->W = p->window; pl->pool = p->pool_kernel; pl->n_seqs = p->n_seqs;
   pl->select_mode = p->select_mode;
+  pl->variant = p->score_variant;
+  pl->key_trim = (p->score_variant & CODECOMP_VARIANT_SOFTMAX_PREFIX) ? p->window : 0;
   pl->span_ratio = p->span_budget_ratio; pl->span_min = p->span_budget_min;
   // two-stage selection keeps the prior out of the scores: structure is handled by the selection itself
   pl->lambda = p->select_mode == CODECOMP_SELECT_TWO_STAGE ? 0.0f : p->prior_weight;
@@ -107,6 +113,8 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   int per = (pl->R + pl->row_splits - 1) / pl->row_splits;
   pl->row_blocks = (per + 31) / 32;
   assign_row_blocks(pl);
+  // the largest head mass is taken per workgroup from whole row blocks: one head per block, all rows in one workgroup
+  if ((pl->variant & CODECOMP_VARIANT_GROUP_MAX) && (pl->W % 32 != 0 || pl->row_splits != 1)) return CODECOMP_EINVAL_MODE;
   pl->lead_tiles = kLeadTiles;
   if (const char* e = getenv("CODECOMP_SCORE_LEAD_TILES")) {   // tuning experiments
     const int v = atoi(e);
@@ -114,7 +122,7 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   }
   int64_t tiles = 0;
   for (int r = 0; r < p->n_seqs; ++r) {
-    int n = p->cu_seqlens_host[r + 1] - p->cu_seqlens_host[r];
+    int n = p->cu_seqlens_host[r + 1] - p->cu_seqlens_host[r] - pl->key_trim;     // >= 0: W <= N_r was checked
     tiles += (n + kTileKeys - 1) / kTileKeys;
   }
   const int64_t problems = (int64_t)pl->L * pl->Hkv * pl->row_splits;

@@ -20,6 +20,8 @@ struct Plan {
   int L, Hq, Hkv, G, d, W, pool, n_seqs;
   float lambda, scale;
   int select_mode;           // CODECOMP_SELECT_*
+  int variant;               // CODECOMP_VARIANT_* flags
+  int key_trim;              // keys at the end of every request that the softmax leaves out (W or 0)
   float span_ratio; int span_min;
   int T, TB;                 // total tokens / total output slots over the packed requests
   int max_n;                 // longest request

@@ -50,6 +50,8 @@ struct ScoreArgs {
   int tiles_per_problem;             // sum over requests of (lead + ceil(N_r / 64))
   int total_tiles;                   // L*Hkv * row_splits * tiles_per_problem
   int stat_wgs;                      // workgroups of the pass-1 launch whose statistics `stats` holds
+  int key_trim;                      // keys at the end of every request left out of the softmax (prefix-only variant)
+  int blocks_per_head;               // largest-head-mass variant: row blocks of one query head (window / 32)
   uint32_t wave_desc[kMaxWaves];     // row block of slot 0 | row block of slot 1 << 8 | halves of slot 1 << 16 (bit 0: first, bit 1: second)
   uint8_t rb_holder[2 * kMaxWaves][2];   // per row block: the (wave * 2 + slot) indices that hold its statistics, 255 = none
   int64_t q_sl, q_ss, q_sh, q_st, kv_sl, kv_sh, kv_st;
@@ -68,14 +70,14 @@ __device__ unsigned char g_simd[2048][8];     // SIMD id of each wave of a workg
 __device__ __forceinline__ bf16x8 frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // Request that holds position `xr` of a (layer*head, row split) sequence; tile_in_seq < 0 inside the lead.
-__device__ __forceinline__ void locate_tile(const int32_t* cu, int n_seqs, int lead, int xr, int& seq, int& tok0, int& n,
-                                            int& tile_in_seq, int& tiles_of_seq) {
+__device__ __forceinline__ void locate_tile(const int32_t* cu, int n_seqs, int lead, int trim, int xr, int& seq, int& tok0,
+                                            int& n, int& tile_in_seq, int& tiles_of_seq) {
   int acc = 0;
   for (int r = 0; r < n_seqs; ++r) {
     const int a = cu[r], b = cu[r + 1];
-    const int nt = (b - a + kTileKeys - 1) / kTileKeys;
+    const int nt = (b - a - trim + kTileKeys - 1) / kTileKeys;      // keys of the request: all but the last `trim`
     if (xr < acc + lead + nt || r == n_seqs - 1) {
-      seq = r; tok0 = a; n = b - a; tile_in_seq = xr - acc - lead; tiles_of_seq = nt;
+      seq = r; tok0 = a; n = b - a - trim; tile_in_seq = xr - acc - lead; tiles_of_seq = nt;
       return;
     }
     acc += lead + nt;
@@ -101,8 +103,10 @@ __device__ __forceinline__ f32x16 mma_step(u32x4 qfrag, u32x4 kfrag, f32x16 acc)
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(qfrag), frag(kfrag), acc, 0, 0, 0);
 }
 
-template <int D, int NW, int PASS>
+// GMAX (pass 2 only): the largest query-head mass of the group instead of the (scaled) sum over its heads.
+template <int D, int NW, int PASS, bool GMAX = false>
 __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(ScoreArgs a) {
+  static_assert(PASS == 2 || !GMAX, "the group reduction happens in pass 2");
   constexpr int NT = NW * 64;
   constexpr int KS = D / 16;                   // MFMA k-steps per logit
   constexpr int ROWB = D * 2 + 16;             // LDS bytes per key row (+16: spreads rows over banks)
@@ -113,8 +117,9 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   static_assert(LDS_ROWS >= kTileKeys, "tile staging");
 
   __shared__ __attribute__((aligned(16))) unsigned char ktile[2][LDS_ROWS * ROWB];
-  // pass 2: column partials of the last four tiles, one row per (wave, half wave)
-  __shared__ float colbuf[PASS == 2 ? 4 : 1][PASS == 2 ? NW * 2 : 1][kTileKeys];
+  // pass 2: column partials of the last four tiles, one row per (wave, half wave); with group_max one
+  // row per (wave, slot, half wave), because the two slots of a wave may belong to different query heads
+  __shared__ float colbuf[PASS == 2 ? 4 : 1][PASS == 2 ? NW * (GMAX ? 4 : 2) : 1][kTileKeys];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -144,12 +149,13 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   const int layer = lz / a.Hkv;
   const int head = lz - layer * a.Hkv;
   int seq, tok0, n, tile_in_seq, tiles_of_seq;
-  locate_tile(a.cu_seqlens, a.n_seqs, a.lead, x - hi * a.tiles_per_problem, seq, tok0, n, tile_in_seq, tiles_of_seq);
+  locate_tile(a.cu_seqlens, a.n_seqs, a.lead, a.key_trim, x - hi * a.tiles_per_problem, seq, tok0, n, tile_in_seq, tiles_of_seq);
   if (tile_in_seq < 0) {                                    // inside the lead: the problem's tiles start after it
     x -= tile_in_seq;
     tile_in_seq = 0;
     if (x >= x_end) break;
   }
+  if (tile_in_seq >= tiles_of_seq) continue;                // a request without keys (prefix-only softmax, N == W)
   const int ntiles = min(x_end - x, tiles_of_seq - tile_in_seq);
   const int kstart = tile_in_seq * kTileKeys;
   const int kend = min(n, kstart + ntiles * kTileKeys);
@@ -251,10 +257,24 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     if constexpr (PASS == 2) {
       if (tile >= 0 && wave == NW - 1) {
         float s = 0.f;
+        if constexpr (!GMAX) {
 #pragma unroll
-        for (int w = 0; w < NW * 2; ++w) s += colbuf[tile & 3][w][lane];
+          for (int w = 0; w < NW * 2; ++w) s += colbuf[tile & 3][w][lane];
+          s *= a.inv_g;
+        } else {
+          // row blocks in order: the blocks of one query head are consecutive; a block's mass is the sum of its
+          // owners' partials (both half waves of each); the head masses are compared, not added
+          float cur = 0.f;
+          for (int rb = 0; rb < a.nb; ++rb) {
+            for (int h = 0; h < 2; ++h) {
+              const int holder = a.rb_holder[rb][h];      // wave * 2 + slot
+              if (holder != 255) cur += colbuf[tile & 3][holder * 2][lane] + colbuf[tile & 3][holder * 2 + 1][lane];
+            }
+            if ((rb + 1) % a.blocks_per_head == 0 || rb == a.nb - 1) { s = fmaxf(s, cur); cur = 0.f; }
+          }
+        }
         const int key = kstart + tile * kTileKeys + lane;
-        if (key < kend) a.uraw[((int64_t)split * a.LH + lz) * a.T + tok0 + key] = s * a.inv_g;
+        if (key < kend) a.uraw[((int64_t)split * a.LH + lz) * a.T + tok0 + key] = s;
       }
     }
   };
@@ -368,8 +388,11 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
         l_run0 = l_run0 * al0 + s0; m_run0 = mn0;
         if constexpr (BOTH) { l_run1 = l_run1 * al1 + s1; m_run1 = mn1; }
       }
-    } else {
+    } else if constexpr (!GMAX) {
       colbuf[ptile & 3][wave * 2 + hf][pkh * 32 + l32] = BOTH ? s0 + s1 : s0;
+    } else {
+      colbuf[ptile & 3][wave * 4 + hf][pkh * 32 + l32] = s0;
+      colbuf[ptile & 3][wave * 4 + 2 + hf][pkh * 32 + l32] = BOTH ? s1 : 0.f;
     }
   };
 
@@ -608,8 +631,13 @@ __global__ __launch_bounds__(256) void score_merge_kernel(ScoreArgs a) {
   const int rb = (row - split * a.nb * 32) >> 5;
   const int hi = lz * a.row_splits + split;
   int tile_off = a.lead;
-  for (int r = 0; r < seq; ++r) tile_off += a.lead + (a.cu_seqlens[r + 1] - a.cu_seqlens[r] + kTileKeys - 1) / kTileKeys;
-  const int nt = (a.cu_seqlens[seq + 1] - a.cu_seqlens[seq] + kTileKeys - 1) / kTileKeys;
+  for (int r = 0; r < seq; ++r)
+    tile_off += a.lead + (a.cu_seqlens[r + 1] - a.cu_seqlens[r] - a.key_trim + kTileKeys - 1) / kTileKeys;
+  const int nt = (a.cu_seqlens[seq + 1] - a.cu_seqlens[seq] - a.key_trim + kTileKeys - 1) / kTileKeys;
+  if (nt == 0) {                           // no key to attend to: nothing reads this normaliser
+    a.lse[((int64_t)lz * a.n_seqs + seq) * a.lrows + row] = 0.f;
+    return;
+  }
   const int x0 = hi * a.tiles_per_problem + tile_off;
   const int g0 = wg_of_tile(x0, a.total_tiles, a.stat_wgs), g1 = wg_of_tile(x0 + nt - 1, a.total_tiles, a.stat_wgs);
   const int p = hi * a.n_seqs + seq;
@@ -634,13 +662,26 @@ struct FinishArgs {
   const int32_t* cu_seqlens;
   float* scores;
   int n_seqs, T, LH, row_splits, pool;
+  int mass_trim;      // window positions at the end of every request that hold no attention mass (prefix-only softmax)
+  int pool_trim;      // window positions at the end of every request that pooling leaves out (prefix-only pooling)
+  int pool_max;       // 1: max pooling
   float lambda, inv_pool;
 };
 
 constexpr int kFinishTile = 1024;     // tokens per workgroup of the finish kernel
 constexpr int kFinishHalo = 512;      // largest supported (pool_kernel - 1) / 2
 
-// scores[lz][j] = (1/k) * sum_{|delta| <= (k-1)/2, inside the request} u[lz][j+delta] + lambda * prior[j]
+__device__ __forceinline__ int request_of(const int32_t* cu, int n_seqs, int j) {
+  int lo = 0, hi = n_seqs;              // cu[lo] <= j < cu[lo+1]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu[mid] <= j) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// scores[lz][j] = pool_{|delta| <= (k-1)/2, inside the request (or its prefix)} u[lz][j+delta] + lambda * prior[j],
+// pool = sum / k (zero padding, divisor always k) or max.
 // One workgroup stages 1024 tokens of u (+ halo, row splits added) in LDS; every output is a direct sum.
 __global__ __launch_bounds__(256) void score_finish_kernel(FinishArgs a) {
   __shared__ float tile[kFinishTile + 2 * kFinishHalo];
@@ -651,7 +692,10 @@ __global__ __launch_bounds__(256) void score_finish_kernel(FinishArgs a) {
   for (int i = tid; i < kFinishTile + 2 * half; i += 256) {
     const int x = base - half + i;
     float val = 0.f;
-    if (x >= 0 && x < a.T)
+    bool has_mass = x >= 0 && x < a.T;
+    if (has_mass && a.mass_trim > 0)      // window positions were never written by the mass pass
+      has_mass = x < a.cu_seqlens[request_of(a.cu_seqlens, a.n_seqs, x) + 1] - a.mass_trim;
+    if (has_mass)
       for (int sp = 0; sp < a.row_splits; ++sp) val += a.uraw[((int64_t)sp * a.LH + lz) * a.T + x];
     tile[i] = val;
   }
@@ -660,16 +704,19 @@ __global__ __launch_bounds__(256) void score_finish_kernel(FinishArgs a) {
   for (int e = 0; e < kFinishTile / 256; ++e) {
     const int j = base + e * 256 + tid;
     if (j >= a.T) continue;
-    int lo = 0, hi = a.n_seqs;          // request containing token j: cu[lo] <= j < cu[lo+1]
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (a.cu_seqlens[mid] <= j) lo = mid; else hi = mid;
-    }
-    const int s0 = a.cu_seqlens[lo], s1 = a.cu_seqlens[lo + 1];
+    const int lo = request_of(a.cu_seqlens, a.n_seqs, j);
+    const int s0 = a.cu_seqlens[lo], s1 = a.cu_seqlens[lo + 1] - a.pool_trim;     // pooling domain [s0, s1)
     const int b0 = max(s0, j - half), b1 = min(s1 - 1, j + half);
-    float sum = 0.f;
-    for (int x = b0; x <= b1; ++x) sum += tile[x - base + half];
-    a.scores[(int64_t)lz * a.T + j] = __builtin_fmaf(a.lambda, a.prior[j], sum * a.inv_pool);
+    float pooled = 0.f;
+    if (j < s1) {
+      if (a.pool_max) {
+        for (int x = b0; x <= b1; ++x) pooled = fmaxf(pooled, tile[x - base + half]);      // masses are >= 0
+      } else {
+        for (int x = b0; x <= b1; ++x) pooled += tile[x - base + half];
+        pooled *= a.inv_pool;
+      }
+    }
+    a.scores[(int64_t)lz * a.T + j] = __builtin_fmaf(a.lambda, a.prior[j], pooled);
   }
 }
 
@@ -702,9 +749,11 @@ template <int D, int NW>
 static int launch_passes(const Plan& pl, ScoreArgs a, hipStream_t stream, unsigned stages) {
   static const int resident1 = resident_workgroups(score_pass_kernel<D, NW, 1>, NW * 64);
   static const int resident2 = resident_workgroups(score_pass_kernel<D, NW, 2>, NW * 64);
+  static const int resident2m = resident_workgroups(score_pass_kernel<D, NW, 2, true>, NW * 64);
   const dim3 block(NW * 64);
   a.stat_wgs = score_grid(pl, resident1);
-  if (stages & CODECOMP_STAGE_ROW_STATS) {
+  const bool any_tile = pl.real_tiles > 0;      // false: prefix-only softmax with no prefix anywhere
+  if ((stages & CODECOMP_STAGE_ROW_STATS) && any_tile) {
     score_pass_kernel<D, NW, 1><<<dim3(a.stat_wgs), block, 0, stream>>>(a);
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
@@ -713,8 +762,11 @@ static int launch_passes(const Plan& pl, ScoreArgs a, hipStream_t stream, unsign
     score_merge_kernel<<<mgrid, dim3(256), 0, stream>>>(a);
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
-  if (stages & CODECOMP_STAGE_MASS) {
-    score_pass_kernel<D, NW, 2><<<dim3(score_grid(pl, resident2)), block, 0, stream>>>(a);
+  if ((stages & CODECOMP_STAGE_MASS) && any_tile) {
+    if (pl.variant & CODECOMP_VARIANT_GROUP_MAX)
+      score_pass_kernel<D, NW, 2, true><<<dim3(score_grid(pl, resident2m)), block, 0, stream>>>(a);
+    else
+      score_pass_kernel<D, NW, 2><<<dim3(score_grid(pl, resident2)), block, 0, stream>>>(a);
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
   return 0;
@@ -752,7 +804,9 @@ int launch_score(const Plan& pl, const void* q, const void* k, const float* prio
   a.q_sl = pl.q_sl; a.q_ss = pl.q_ss; a.q_sh = pl.q_sh; a.q_st = pl.q_st;
   a.kv_sl = pl.kv_sl; a.kv_sh = pl.kv_sh; a.kv_st = pl.kv_st;
   a.c = pl.scale * 1.4426950408889634f;
-  a.inv_g = 1.0f / (float)pl.G;
+  a.inv_g = (pl.variant & CODECOMP_VARIANT_GROUP_SUM) ? 1.0f : 1.0f / (float)pl.G;
+  a.key_trim = pl.key_trim;
+  a.blocks_per_head = (pl.variant & CODECOMP_VARIANT_GROUP_MAX) ? pl.W / 32 : 1;
   int rc = pl.d == 128 ? dispatch_waves<128>(pl, a, stream, stages) : dispatch_waves<64>(pl, a, stream, stages);
   if (rc) return rc;
 #if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
@@ -787,6 +841,9 @@ int launch_score(const Plan& pl, const void* q, const void* k, const float* prio
   f.uraw = a.uraw; f.prior = prior; f.cu_seqlens = pl.cu_seqlens_dev; f.scores = scores;
   f.n_seqs = pl.n_seqs; f.T = pl.T; f.LH = pl.L * pl.Hkv; f.row_splits = pl.row_splits; f.pool = pl.pool;
   f.lambda = pl.lambda; f.inv_pool = 1.0f / (float)pl.pool;
+  f.mass_trim = pl.key_trim;
+  f.pool_trim = (pl.variant & CODECOMP_VARIANT_POOL_PREFIX) ? pl.W : 0;
+  f.pool_max = (pl.variant & CODECOMP_VARIANT_POOL_MAX) ? 1 : 0;
   score_finish_kernel<<<dim3((pl.T + kFinishTile - 1) / kFinishTile, pl.L * pl.Hkv), dim3(256), 0, stream>>>(f);
   if (hipError_t e = hipGetLastError()) return (int)e;
   return 0;

@@ -37,8 +37,9 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_layout_matches_header():
-    # 10 x 4-byte fields, 4 pointers, 10 x int64 strides, span budget (float + int32)
-    assert C.sizeof(b.codecomp_params) == 40 + 32 + 80 + 8
+    # 10 x 4-byte fields, 4 pointers, 10 x int64 strides, span budget (float + int32), variant flags + reserved
+    assert C.sizeof(b.codecomp_params) == 40 + 32 + 80 + 8 + 8
+    assert b.codecomp_params.score_variant.offset == 160
     assert b.codecomp_params.span_budget_ratio.offset == 152
     assert b.codecomp_params.cu_seqlens_host.offset == 40
     assert b.codecomp_params.q_stride_layer.offset == 72
@@ -55,6 +56,9 @@ def good(**over):
 def test_valid_params_and_workspace_size():
     p = good()
     assert b.codecomp_validate(p) == 0
+    for variant in (1, 4, 8, 16, 1 | 4 | 8 | 16):
+        assert b.codecomp_validate(good(score_variant=variant)) == 0
+    assert b.codecomp_validate(good(score_variant=2 | 4, window=32, cu_budgets_host=np.array([0, 40, 80]))) == 0
     ws = b.codecomp_workspace_bytes(p)
     assert ws > 0 and ws % 256 == 0
     # the raw attention mass alone needs L * H_kv * T floats
@@ -81,6 +85,12 @@ def test_valid_params_and_workspace_size():
     (dict(kv_stride_tok=100), -2),                                  # not a multiple of 8 elements
     (dict(kv_stride_tok=64), -2),                                   # rows would overlap
     (dict(select_mode=2), -11),
+    (dict(score_variant=32), -11),                                     # unknown flag
+    (dict(score_variant=1 | 2), -11),                                  # group sum and max together
+    (dict(score_variant=2), -11),                                      # group max needs window % 32 == 0 (16 here)
+    (dict(score_variant=2, window=64, n_q_heads=18, cu_seqlens_host=np.array([0, 100, 300]),
+          cu_budgets_host=np.array([0, 70, 140])), -11),                # group max needs all rows in one workgroup (9 * 64 > 512)
+    (dict(reserved=1), -11),
     (dict(select_mode=1, span_budget_ratio=1.5), -11),
     (dict(select_mode=1, span_budget_ratio=0.5, span_budget_min=-1), -11),
     (dict(pool_kernel=1027), -5),

@@ -14,12 +14,20 @@ def _binding():
     return binding
 
 
-def run_case(w, *, fused=True, check_oracle=True):
+def oracle_variant(flags: int) -> dict:
+    """Oracle keyword arguments for a set of CODECOMP_VARIANT_* flags."""
+    return dict(group_reduce="sum" if flags & 1 else "max" if flags & 2 else "mean",
+                pool_mode="max" if flags & 4 else "avg",
+                softmax_domain="prefix" if flags & 8 else "all",
+                pool_domain="prefix" if flags & 16 else "row")
+
+
+def run_case(w, *, fused=True, check_oracle=True, variant=0):
     """Runs the three steps (or the fused call) and compares every stage with the oracle."""
     import torch
     b = _binding()
     q, k, v, prior = wl.make_all(w)
-    prob = b.DeviceProblem(w, q, k, v, prior)
+    prob = b.DeviceProblem(w, q, k, v, prior, score_variant=variant)
     if fused:
         prob.compress()
     else:
@@ -39,7 +47,8 @@ def run_case(w, *, fused=True, check_oracle=True):
     if not check_oracle:
         return prob, sc_gpu, idx_gpu
     # scores and index sets against the fp64 oracle
-    sc_ref = orc.score_packed(q, k, prior, cu, pool_kernel=w.pool_kernel, prior_weight=w.prior_weight)
+    sc_ref = orc.score_packed(q, k, prior, cu, pool_kernel=w.pool_kernel, prior_weight=w.prior_weight,
+                              **oracle_variant(variant))
     pu.assert_scores_close(sc_gpu, sc_ref)
     idx_ref = orc.select_packed(sc_ref, cu, cb, w.window)
     for l in range(w.n_layers):
@@ -105,6 +114,31 @@ def test_row_blocks_shared_between_waves(group, window):
     every tile); their statistics are merged per row."""
     run_case(wl.scaled(wl.qwen7b_32k(), n_layers=1, seqlens=[1500, 230], budgets=[window + 50, window + 3], window=window,
                        n_q_heads=2 * group, n_kv_heads=2))
+
+
+@pytest.mark.parametrize("variant", [1, 4, 8, 16, 1 | 4, 8 | 16, 1 | 4 | 8 | 16, 2, 2 | 4 | 8 | 16])
+def test_score_tail_variants(variant):
+    """Group sum / max, max pooling, prefix-only softmax and pooling, alone and combined: 448 rows (shared row
+    blocks, 14 blocks = 7 heads of 2), several requests, one of them nothing but its window."""
+    w = wl.scaled(wl.qwen7b_32k(), n_layers=2, seqlens=[1500, 64, 700, 65], budgets=[150, 64, 90, 64], n_kv_heads=2,
+                  n_q_heads=14)
+    run_case(w, variant=variant)
+    run_case(wl.scaled(wl.tiny(), seqlens=[1000], budgets=[100], prior_weight=0.0), variant=variant, fused=False)
+
+
+def test_prefix_softmax_without_any_prefix():
+    """Every request is only its window: no key to attend to, all masses zero, scores = lambda * prior."""
+    import torch
+    b = _binding()
+    w = wl.scaled(wl.tiny(), seqlens=[32, 32], budgets=[32, 32])
+    q, k, v, prior = wl.make_all(w)
+    prob = b.DeviceProblem(w, q, k, v, prior, score_variant=b.VARIANT_SOFTMAX_PREFIX)
+    prob.workspace.fill_(0xFF)
+    prob.compress()
+    torch.cuda.synchronize()
+    sc = prob.scores.cpu().numpy()
+    np.testing.assert_array_equal(sc, np.broadcast_to((np.float32(w.prior_weight) * prior)[None, None, :], sc.shape))
+    assert np.array_equal(prob.idx.cpu().numpy()[0, 0], np.concatenate([np.arange(32), np.arange(32)]))
 
 
 @pytest.mark.parametrize("kw", [
