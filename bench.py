@@ -63,7 +63,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="qwen7b_32k")
-    ap.add_argument("--cpu-layers", type=int, default=12, help="layers the CPU oracle is timed and compared on")
+    ap.add_argument("--cpu-layers", type=int, default=28, help="layers the CPU oracle is timed and compared on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (experiments only)")
     ap.add_argument("--calibrate-copy", action="store_true",
