@@ -623,16 +623,23 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 // One thread per (layer*head, request, row): log2-sum-exp over the segments that cover the request and
 // over the (at most two) wave slots that hold a share of the row's keys.
 __global__ __launch_bounds__(256) void score_merge_kernel(ScoreArgs a) {
+  __shared__ int part[256 / 64];
   const int row = blockIdx.x * blockDim.x + threadIdx.x;
   const int seq = blockIdx.y;
   const int lz = blockIdx.z;
+  // positions of the earlier requests in a problem's sequence: summed by the whole workgroup
+  int mine = 0;
+  for (int r = threadIdx.x; r < seq; r += 256)
+    mine += a.lead + (a.cu_seqlens[r + 1] - a.cu_seqlens[r] - a.key_trim + kTileKeys - 1) / kTileKeys;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mine;
+  __syncthreads();
+  const int tile_off = a.lead + part[0] + part[1] + part[2] + part[3];
   if (row >= a.lrows) return;
   const int split = row / (a.nb * 32);
   const int rb = (row - split * a.nb * 32) >> 5;
   const int hi = lz * a.row_splits + split;
-  int tile_off = a.lead;
-  for (int r = 0; r < seq; ++r)
-    tile_off += a.lead + (a.cu_seqlens[r + 1] - a.cu_seqlens[r] - a.key_trim + kTileKeys - 1) / kTileKeys;
   const int nt = (a.cu_seqlens[seq + 1] - a.cu_seqlens[seq] - a.key_trim + kTileKeys - 1) / kTileKeys;
   if (nt == 0) {                           // no key to attend to: nothing reads this normaliser
     a.lse[((int64_t)lz * a.n_seqs + seq) * a.lrows + row] = 0.f;

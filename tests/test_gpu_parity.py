@@ -321,3 +321,12 @@ def test_logits_that_outrun_the_first_tile_reference():
     assert (np.abs(sc[big] - ref[big]) / ref[big]).max() < 1e-3
     mass = (sc.astype(np.float64) - w.prior_weight * prior).sum(axis=2)
     assert np.all(np.abs(mass - w.window) < 0.02 * w.window)
+
+
+def test_many_short_requests():
+    """300 packed requests of 40..167 tokens: every per-request lookup (tile sequence, merge, pooling, select) at scale."""
+    rng = np.random.default_rng(5)
+    lens = [int(x) for x in rng.integers(40, 168, size=300)]
+    w = wl.scaled(wl.ragged_agentic(), seqlens=lens, budgets=[max(32, n // 3) for n in lens], window=32,
+                  n_kv_heads=2, n_q_heads=4)
+    run_case(w)
