@@ -60,8 +60,9 @@ def read_traffic(name: str):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200,
+                    help="timed steps; the bracketing synchronisation costs a fixed ~1.5 ms, so few steps overstate the step time")
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="qwen7b_32k")
     ap.add_argument("--cpu-layers", type=int, default=28, help="layers the CPU oracle is timed and compared on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -108,10 +109,12 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    # per-kernel durations: the same kernels enqueued one by one with events between them
+    # per-kernel durations: the same kernels enqueued one by one with events between them, all steps
+    # back to back like the fused loop above (one synchronisation at the end: same clocks, same heat)
     names = ["score_row_stats", "score_row_merge", "score_mass", "score_finish", "select", "gather"]
     stages = [binding.STAGE_ROW_STATS, binding.STAGE_ROW_MERGE, binding.STAGE_MASS, binding.STAGE_FINISH]
     acc = dict.fromkeys(names, 0.0)
+    all_ev = []
     for _ in range(args.steps):
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)]
         ev[0].record()
@@ -120,7 +123,9 @@ def main() -> int:
             ev[i + 1].record()
         prob.select(); ev[5].record()
         prob.gather(); ev[6].record()
-        torch.cuda.synchronize()
+        all_ev.append(ev)
+    torch.cuda.synchronize()
+    for ev in all_ev:
         for i, nm in enumerate(names):
             acc[nm] += ev[i].elapsed_time(ev[i + 1])
     stage_ms = {nm: acc[nm] / args.steps for nm in names}
