@@ -94,7 +94,7 @@ typedef struct codecomp_params {
  *   GROUP_SUM      the masses of the G query heads of a KV head are summed, not averaged;
  *   GROUP_MAX      the largest head mass wins (needs window % 32 == 0 and G * window <= 512);
  *   POOL_MAX       max pooling over the pool_kernel neighbours instead of their average;
- *   SOFTMAX_PREFIX the softmax runs over the N - W context keys only (the K "in R^{L_c x d}" of the
+ *   SOFTMAX_PREFIX the softmax runs over the N - W context keys only (the K with one row per context token of the
  *                  section); window positions get no attention mass;
  *   POOL_PREFIX    pooling stays inside the N - W context positions; window positions get none.
  * GROUP_SUM and GROUP_MAX exclude each other.  Unknown bits are rejected (CODECOMP_EINVAL_MODE). */
@@ -161,7 +161,8 @@ int codecomp_score_stages(const void* q_obs, const void* k, const float* prior, 
 /* Per (layer, KV head, request): keep tokens N_r-W .. N_r-1, add the B_r - W tokens of the
  * prefix [0, N_r - W) with the largest scores (equal scores: the lower index wins; scores are
  * ordered as IEEE floats, -0 == +0, NaN unspecified), write the B_r indices in ascending
- * order.  Follows "retain the top-ranked context tokens ... up to the remaining chunk budget". */
+ * order.  Follows section "Attention-based KV Cache Compression": the best-scored context tokens are kept
+ * until the remaining budget of the chunk is used up. */
 int codecomp_select(const float* scores, const codecomp_params* params, int32_t* idx,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 

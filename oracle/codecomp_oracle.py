@@ -23,8 +23,8 @@ What it follows (paper sections / equations):
     PARITY UNPINNED BY THE PAPER for this combination rule: no worked example or printed
     number distinguishes the additive reading from the two-stage rule.  It is pinned only
     by closed forms (lambda = 0, lambda large) and brute force.
-  * "We retain the top-ranked context tokens ... up to the remaining chunk budget" and
-    "Compression is applied independently at each transformer layer": selection is per
+  * The same section keeps the best-scored context tokens until the chunk's remaining budget is
+    used up, and compresses every transformer layer on its own: selection is per
     layer (and here per KV head), and the compact cache holds the retained K/V rows in
     their original order.
 
@@ -41,7 +41,7 @@ defaults are the readings above):
     mass wins, instead of averaged;
   - pool_mode "max": max pooling instead of the appendix's average pooling;
   - softmax_domain "prefix": the softmax of section "Attention-based KV Cache Compression"
-    runs over the context keys only (its K "in R^{L_c x d}"), i.e. the N - W keys before the
+    runs over the context keys only (the section gives K one row per context token), i.e. the N - W keys before the
     observation window; window columns get no mass;
   - pool_domain "prefix": pooling never looks across the boundary between context and window.
 

@@ -1,6 +1,6 @@
 // Select step: per (layer, KV head, request) keep the last W tokens and the B - W best tokens
 // of the prefix [0, N - W); equal scores go to the lower index; indices come out ascending
-// ("retain the top-ranked context tokens ... up to the remaining chunk budget").
+// (section "Attention-based KV Cache Compression": the best-scored context tokens are kept until the budget is used up).
 //
 // One workgroup of 1024 threads owns one problem.  An MSB-first radix select over order-preserving
 // integer images of the float scores (digits of 11, 11 and 10 bits, LDS histogram) finds the score
@@ -16,7 +16,7 @@
 //                (sections "Span-Level Structural Protection" and "Attention-based KV Cache
 //                Compression"): stage 1 keeps up to B_span = min(Bp, max(B_min, floor(rho * Bp)))
 //                prefix tokens with prior > 0, largest prior first (ties: first in sequence, which for a
-//                binary prior is "the first tokens of P"), Bp = B - W; stage 2 fills the remaining
+//                binary prior is the paper's rule for an overfull protected set: its first tokens), Bp = B - W; stage 2 fills the remaining
 //                Bp - |P| slots with the best pooled-attention tokens not in P.
 #include "plan.h"
 
