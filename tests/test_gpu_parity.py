@@ -330,3 +330,37 @@ def test_many_short_requests():
     w = wl.scaled(wl.ragged_agentic(), seqlens=lens, budgets=[max(32, n // 3) for n in lens], window=32,
                   n_kv_heads=2, n_q_heads=4)
     run_case(w)
+
+
+def test_compress_replays_from_a_hip_graph():
+    """The fused call captured into a graph: no allocation, no synchronisation, no memset inside.  Replays are
+    interleaved with eager work on other inputs and must reproduce the eager result bit for bit every time."""
+    import torch
+    b = _binding()
+    w = wl.scaled(wl.qwen7b_32k(), n_layers=2, seqlens=[3000, 700], budgets=[300, 100])
+    q, k, v, prior = wl.make_all(w)
+    prob = b.DeviceProblem(w, q, k, v, prior)
+    prob.compress()                                   # eager reference (and first-call set-up outside the capture)
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (prob.scores, prob.idx, prob.k_out, prob.v_out)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        prob.compress()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        prob.compress()
+    other = b.DeviceProblem(wl.tiny(), *wl.make_all(wl.tiny()))
+    for _ in range(3):
+        for t in (prob.scores, prob.k_out, prob.v_out):
+            t.zero_()
+        prob.idx.fill_(-1)
+        prob.workspace.fill_(0xFF)
+        other.compress()                              # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((prob.scores, prob.idx, prob.k_out, prob.v_out), ref):
+            assert torch.equal(got.view(torch.uint8) if got.dtype == torch.bfloat16 else got,
+                               want.view(torch.uint8) if want.dtype == torch.bfloat16 else want)
