@@ -45,7 +45,14 @@ struct SelectShared {
 #ifndef CODECOMP_SELECT_AGGREGATE
 #define CODECOMP_SELECT_AGGREGATE 1
 #endif
+// CROWDED = false (the digits after the first): only the few candidates that share the prefix found so far
+// take part, and plain atomics are cheaper than the ballots (measured: 10% off the kernel).
+template <bool CROWDED>
 __device__ __forceinline__ void hist_add(SelectShared& sh, bool match, uint32_t bin) {
+  if constexpr (!CROWDED) {
+    if (match) atomicAdd(&sh.hist[bin], 1u);
+    return;
+  }
 #if CODECOMP_SELECT_AGGREGATE
   const int lane = threadIdx.x & 63;
   unsigned long long pend = __ballot(match);
@@ -181,7 +188,8 @@ __device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emi
 #pragma unroll
         for (int s = 0; s < ITEMS; ++s) {
           const bool match = ((elig >> s) & 1ull) && (keys[s] & himask) == prefix;
-          hist_add(sh, match, (keys[s] >> shift) & (uint32_t)(nbins - 1));
+          if (pass == 0) hist_add<true>(sh, match, (keys[s] >> shift) & (uint32_t)(nbins - 1));
+          else hist_add<false>(sh, match, (keys[s] >> shift) & (uint32_t)(nbins - 1));
         }
       } else {
         const int npad = (npre + NT - 1) / NT * NT;   // uniform trip counts: every lane takes part in the ballots
@@ -197,7 +205,8 @@ __device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emi
           }
 #pragma unroll
           for (int u = 0; u < UNR; ++u)
-            hist_add(sh, v8[u] && (k8[u] & himask) == prefix, (k8[u] >> shift) & (uint32_t)(nbins - 1));
+            if (pass == 0) hist_add<true>(sh, v8[u] && (k8[u] & himask) == prefix, (k8[u] >> shift) & (uint32_t)(nbins - 1));
+            else hist_add<false>(sh, v8[u] && (k8[u] & himask) == prefix, (k8[u] >> shift) & (uint32_t)(nbins - 1));
         }
       }
       hist_pick(sh, nbins, shift, prefix, remaining);
