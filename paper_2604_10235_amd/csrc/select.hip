@@ -32,41 +32,28 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 constexpr int kSelTileItems = 4;    // consecutive candidates per thread inside one ordered tile
 constexpr int kSelTile = kSelectThreads * kSelTileItems;
 
+constexpr int kHistCopies = 8;      // private copies of the first-digit histogram, picked by lane % 8
+constexpr int kHistStride = 2049;   // odd stride: equal bins of different copies sit in different banks
+
 struct SelectShared {
-  unsigned int hist[2048];
+  unsigned int hist[kHistCopies * kHistStride];
   unsigned int prefix, need;
   int wave_sure[kSelectThreads / 64], wave_tie[kSelectThreads / 64];
   int tile_sure, tile_tie;
+  // class (0 out, 1 tied at the cut, 2 in) of every register-resident candidate, one byte each, indexed by
+  // candidate: written in the load layout, read back as runs of consecutive candidates per thread
+  unsigned int cls_words[kSelectThreads * 64 / 4];
 };
 
-// One candidate into the digit histogram.  Score distributions are concentrated, so lanes that share a
-// bin with the first pending lane are counted with one atomic; the rest take one atomic each.
-// Every lane of the wave must call it (ballots).
-#ifndef CODECOMP_SELECT_AGGREGATE
-#define CODECOMP_SELECT_AGGREGATE 1
-#endif
-// CROWDED = false (the digits after the first): only the few candidates that share the prefix found so far
-// take part, and plain atomics are cheaper than the ballots (measured: 10% off the kernel).
+// One candidate into the digit histogram.  CROWDED (the first digit: every candidate takes part and the scores
+// crowd into a few dozen bins): LDS atomics of one instruction that hit the same address are served one after
+// the other, so each lane adds to one of kHistCopies private copies (lane % 8) and at most 8 lanes can collide;
+// the copies are summed when the bin is picked.  Ballot-based aggregation was tried first: its serial
+// scalar/vector control flow cost about 1000 cycles per candidate slot and workgroup.  Later digits: only the
+// few candidates that share the prefix take part, one copy.
 template <bool CROWDED>
 __device__ __forceinline__ void hist_add(SelectShared& sh, bool match, uint32_t bin) {
-  if constexpr (!CROWDED) {
-    if (match) atomicAdd(&sh.hist[bin], 1u);
-    return;
-  }
-#if CODECOMP_SELECT_AGGREGATE
-  const int lane = threadIdx.x & 63;
-  unsigned long long pend = __ballot(match);
-  if (pend != 0) {
-    const int leader = __ffsll(pend) - 1;
-    const uint32_t lb = __shfl(bin, leader);
-    const unsigned long long same = __ballot(match && bin == lb) & pend;
-    if (lane == leader) atomicAdd(&sh.hist[lb], (unsigned int)__popcll(same));
-    pend &= ~same;
-  }
-  if ((pend >> lane) & 1ull) atomicAdd(&sh.hist[bin], 1u);
-#else
-  if (match) atomicAdd(&sh.hist[bin], 1u);
-#endif
+  if (match) atomicAdd(&sh.hist[(CROWDED ? (threadIdx.x & (kHistCopies - 1)) * kHistStride : 0) + bin], 1u);
 }
 
 __device__ __forceinline__ int pass_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
@@ -75,19 +62,29 @@ __device__ __forceinline__ uint32_t pass_himask(int pass) {
   return pass == 0 ? 0u : (0xFFFFFFFFu << (pass == 1 ? 21 : 10));
 }
 
-__device__ __forceinline__ void hist_clear(SelectShared& sh, int nbins) {
-  for (int b = threadIdx.x; b < nbins; b += kSelectThreads) sh.hist[b] = 0;
+__device__ __forceinline__ void hist_clear(SelectShared& sh, int nbins, int copies) {
+  for (int b = threadIdx.x; b < (copies - 1) * kHistStride + nbins; b += kSelectThreads) sh.hist[b] = 0;
   __syncthreads();
 }
 
 // After a digit pass: the bin holding the `remaining`-th largest candidate; fixes that digit in `prefix`
-// and reduces `remaining` to the rank inside the bin.  All threads call it.
-__device__ __forceinline__ void hist_pick(SelectShared& sh, int nbins, int shift, uint32_t& prefix, uint32_t& remaining) {
+// and reduces `remaining` to the rank inside the bin.  All threads call it.  No step waits for an LDS
+// read that depends on the previous one: the copies are summed by all threads, wave 0 finds the lane whose
+// group of bins holds the rank (suffix sums over lanes), then the bin inside that group the same way.
+__device__ __forceinline__ void hist_pick(SelectShared& sh, int nbins, int copies, int shift, uint32_t& prefix,
+                                          uint32_t& remaining) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   __syncthreads();
+  if (copies > 1) {                    // totals of the private copies into copy 0 (a thread touches only its own bins)
+    for (int b = threadIdx.x; b < nbins; b += kSelectThreads) {
+      unsigned int c = 0;
+      for (int k = 0; k < copies; ++k) c += sh.hist[k * kHistStride + b];
+      sh.hist[b] = c;
+    }
+    __syncthreads();
+  }
   if (wave == 0) {
-    // lane owns bins [lane*per, lane*per+per); walk from the top bin down until `remaining` is covered
-    const int per = nbins / 64;
+    const int per = nbins / 64;        // lane owns bins [lane*per, lane*per+per), per <= 32
     unsigned int mine = 0;
     for (int i = 0; i < per; ++i) mine += sh.hist[lane * per + i];
     unsigned int run = mine;           // inclusive suffix sum over lanes
@@ -97,16 +94,21 @@ __device__ __forceinline__ void hist_pick(SelectShared& sh, int nbins, int shift
       if (lane + off < 64) run += o;
     }
     const unsigned int above = run - mine;   // count in bins owned by higher lanes
-    if (above < remaining && remaining <= above + mine) {   // exactly one lane
-      unsigned int acc = above;
-      int bin = per - 1;
-      for (; bin > 0; --bin) {
-        const unsigned int cnt = sh.hist[lane * per + bin];
-        if (acc + cnt >= remaining) break;
-        acc += cnt;
-      }
-      sh.prefix = prefix | ((uint32_t)(lane * per + bin) << shift);
-      sh.need = remaining - acc;       // rank inside the chosen bin
+    const unsigned long long hit = __ballot(above < remaining && remaining <= above + mine);   // exactly one lane
+    const int owner = __ffsll(hit) - 1;
+    const unsigned int above_owner = __builtin_amdgcn_readlane(above, owner);
+    // the bins of the owner, one per lane
+    const unsigned int c = lane < per ? sh.hist[owner * per + lane] : 0u;
+    unsigned int suf = c;              // inclusive suffix sum over the owner's bins
+#pragma unroll
+    for (int off = 1; off < 32; off <<= 1) {
+      const unsigned int o = __shfl_down(suf, off);
+      if (lane + off < 64) suf += o;
+    }
+    const unsigned int higher = above_owner + suf - c;      // candidates in bins above this one
+    if (lane < per && higher < remaining && remaining <= higher + c) {   // exactly one lane
+      sh.prefix = prefix | ((uint32_t)(owner * per + lane) << shift);
+      sh.need = remaining - higher;    // rank inside the chosen bin
     }
   }
   __syncthreads();
@@ -183,7 +185,8 @@ __device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emi
     for (int pass = 0; pass < 3; ++pass) {
       const int shift = pass_shift(pass), nbins = pass_bins(pass);
       const uint32_t himask = pass_himask(pass);
-      hist_clear(sh, nbins);
+      const int copies = pass == 0 ? kHistCopies : 1;
+      hist_clear(sh, nbins, copies);
       if constexpr (ITEMS > 0) {
 #pragma unroll
         for (int s = 0; s < ITEMS; ++s) {
@@ -209,7 +212,7 @@ __device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emi
             else hist_add<false>(sh, v8[u] && (k8[u] & himask) == prefix, (k8[u] >> shift) & (uint32_t)(nbins - 1));
         }
       }
-      hist_pick(sh, nbins, shift, prefix, remaining);
+      hist_pick(sh, nbins, copies, shift, prefix, remaining);
     }
     tau = prefix;
     ties = (int)remaining;
@@ -237,17 +240,46 @@ __device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emi
     carry_sure += ts; carry_tie += tt;
   };
   if constexpr (ITEMS > 0) {
+    // The classes go through LDS so that every thread ends up with ITEMS consecutive candidates: one workgroup
+    // prefix sum instead of one per tile, and each thread writes its admitted indices to consecutive places.
+    constexpr int T4 = ITEMS / kSelTileItems;
 #pragma unroll
-    for (int t = 0; t < ITEMS / kSelTileItems; ++t) {
-      if (t < ntiles) {                        // uniform
-        int cls[kSelTileItems];
+    for (int t = 0; t < T4; ++t) {
+      unsigned int word = 0;
 #pragma unroll
-        for (int e = 0; e < kSelTileItems; ++e) {
-          const int s = t * kSelTileItems + e;
-          const bool el = (elig >> s) & 1ull, fo = (forc >> s) & 1ull;
-          cls[e] = fo ? 2 : (el ? (keys[s] > tau ? 2 : (keys[s] == tau ? 1 : 0)) : 0);
+      for (int e = 0; e < kSelTileItems; ++e) {
+        const int s = t * kSelTileItems + e;
+        const bool el = (elig >> s) & 1ull, fo = (forc >> s) & 1ull;
+        const unsigned int c = fo ? 2u : (el ? (keys[s] > tau ? 2u : (keys[s] == tau ? 1u : 0u)) : 0u);
+        word |= c << (8 * e);
+      }
+      sh.cls_words[t * kSelectThreads + tid] = word;       // candidates 4 * (t * 1024 + tid) .. + 3
+    }
+    __syncthreads();
+    unsigned int mine[T4];
+    int nsure = 0, ntie = 0;
+#pragma unroll
+    for (int t = 0; t < T4; ++t) {
+      mine[t] = sh.cls_words[tid * T4 + t];                // candidates tid * ITEMS + 4 t .. + 3
+#pragma unroll
+      for (int e = 0; e < kSelTileItems; ++e) {
+        const unsigned int c = (mine[t] >> (8 * e)) & 255u;
+        nsure += c == 2u; ntie += c == 1u;
+      }
+    }
+    int ps, pt, ts, tt;
+    tile_scan(sh, nsure, ntie, ps, pt, ts, tt);
+#pragma unroll
+    for (int t = 0; t < T4; ++t) {
+#pragma unroll
+      for (int e = 0; e < kSelTileItems; ++e) {
+        const int j = tid * ITEMS + t * kSelTileItems + e;
+        const unsigned int c = (mine[t] >> (8 * e)) & 255u;
+        if (j < npre) {
+          const bool admitted = c == 2u || (c == 1u && pt < ties);
+          emit(j, admitted, ps + min(pt, ties));
         }
-        do_tile(t, cls);
+        ps += c == 2u; pt += c == 1u;
       }
     }
   } else {
