@@ -165,15 +165,21 @@ __device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emi
   unsigned long long elig = 0, forc = 0;       // one bit per register slot
   // slot s of this thread holds candidate j = (s / 4) * kSelTile + tid * 4 + (s % 4): tiles in order, 4 consecutive
   if constexpr (ITEMS > 0) {
+    if (npre > 0) {                            // the same for every thread
+      // unconditional loads (index clamped into the row) so that all of them are in flight together
 #pragma unroll
-    for (int s = 0; s < ITEMS; ++s) {
-      const int j = (s / kSelTileItems) * kSelTile + tid * kSelTileItems + (s % kSelTileItems);
-      keys[s] = 0u;
-      if (j < npre) {
-        keys[s] = src.key(j);
-        if (src.eligible(j)) elig |= 1ull << s;
-        if (src.forced(j)) forc |= 1ull << s;
+      for (int s = 0; s < ITEMS; ++s) {
+        const int j = (s / kSelTileItems) * kSelTile + tid * kSelTileItems + (s % kSelTileItems);
+        const int jc = j < npre ? j : npre - 1;
+        const uint32_t key = src.key(jc);
+        const bool el = src.eligible(jc), fo = src.forced(jc);
+        keys[s] = j < npre ? key : 0u;
+        if (j < npre && el) elig |= 1ull << s;
+        if (j < npre && fo) forc |= 1ull << s;
       }
+    } else {
+#pragma unroll
+      for (int s = 0; s < ITEMS; ++s) keys[s] = 0u;
     }
   }
 
