@@ -166,26 +166,6 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   ++nseg_;
 #endif
 
-  // ---- this wave's query rows as MFMA fragments
-  u32x4 qf[2][KS];
-  {
-    const uint16_t* qb = a.q + (int64_t)layer * a.q_sl + (int64_t)seq * a.q_ss;
-#pragma unroll
-    for (int sl = 0; sl < 2; ++sl) {
-      const int row = split_row0 + rb_of[sl] * 32 + l32;
-      const bool ok = row < a.R && (sl == 0 || halves1 != 0);
-      const int g = ok ? row / a.W : 0;
-      const int t = ok ? row - g * a.W : 0;
-      const uint16_t* p = qb + (int64_t)(head * a.G + g) * a.q_sh + (int64_t)t * a.q_st + hf * 8;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        u32x4 v = *reinterpret_cast<const u32x4*>(p + ks * 16);     // row 0 of the group when !ok: in bounds
-        if (!ok) v = u32x4{0, 0, 0, 0};
-        qf[sl][ks] = v;
-      }
-    }
-  }
-
   // ---- K tile staging: global -> registers -> LDS.  Rows past the end of the chunk re-read its
   // last key (always in bounds); such columns are masked (pass 1) or never stored (pass 2).
   const uint16_t* kb = a.k + (int64_t)layer * a.kv_sl + (int64_t)head * a.kv_sh + (int64_t)tok0 * a.kv_st;
@@ -230,6 +210,29 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     const int cidx = tid + i * NT;                                                                  \
     const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;                               \
     *reinterpret_cast<u32x4*>(&ktile[BUF][row * ROWB + col * 16]) = ST[i];                          \
+  }
+
+  // The first K tile of the segment is sent for before the query rows, so that both arrive in one round trip.
+  CODECOMP_GLOAD(kstart, stage)
+
+  // ---- this wave's query rows as MFMA fragments
+  u32x4 qf[2][KS];
+  {
+    const uint16_t* qb = a.q + (int64_t)layer * a.q_sl + (int64_t)seq * a.q_ss;
+#pragma unroll
+    for (int sl = 0; sl < 2; ++sl) {
+      const int row = split_row0 + rb_of[sl] * 32 + l32;
+      const bool ok = row < a.R && (sl == 0 || halves1 != 0);
+      const int g = ok ? row / a.W : 0;
+      const int t = ok ? row - g * a.W : 0;
+      const uint16_t* p = qb + (int64_t)(head * a.G + g) * a.q_sh + (int64_t)t * a.q_st + hf * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        u32x4 v = *reinterpret_cast<const u32x4*>(p + ks * 16);     // row 0 of the group when !ok: in bounds
+        if (!ok) v = u32x4{0, 0, 0, 0};
+        qf[sl][ks] = v;
+      }
+    }
   }
 
   const float c = a.c;
@@ -489,12 +492,12 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 
   // The whole chunk: prologue (tile 0 into LDS buffer 0, tile 1 into the staging registers, first
   // fragments), the tiles, and the softmax of the very last sub-tile.
-  auto run_chunk = [&](auto fast, auto a1, auto b1) __attribute__((always_inline)) {
+  auto run_chunk = [&](auto fast, auto a1, auto b1, auto reload) __attribute__((always_inline)) {
     // the first phase consumes a sub-tile that does not exist: -inf logits add nothing to any sum
 #pragma unroll
     for (int v = 0; v < 16; ++v) { accB0[v] = -INFINITY; accB1[v] = -INFINITY; }
     m_run0 = NEG_BIG; m_run1 = NEG_BIG; l_run0 = 0.f; l_run1 = 0.f; mc0 = 0.f; mc1 = 0.f;
-    CODECOMP_GLOAD(kstart, stage)
+    if constexpr (decltype(reload)::value) CODECOMP_GLOAD(kstart, stage)      // a second run: tile 0 again
     CODECOMP_SSTORE(0, stage)
     CODECOMP_GLOAD(kstart + kTileKeys, stage)
     if constexpr (DEEP) CODECOMP_GLOAD(kstart + 2 * kTileKeys, stage2)
@@ -547,15 +550,15 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   auto run_wave = [&](auto a1, auto b1) __attribute__((always_inline)) {
     if constexpr (PASS == 1) {
 #ifndef CODECOMP_PASS1_SAFE_ONLY
-      run_chunk(std::true_type{}, a1, b1);
+      run_chunk(std::true_type{}, a1, b1, std::false_type{});
       // a row that saw no key at all keeps the reference -1e30: its empty sum is 0, not a failure
       const bool bad = !(l_run0 <= 3.0e38f) || !(l_run1 <= 3.0e38f);     // inf or NaN: a logit outran the reference
-      if (__syncthreads_or(bad)) run_chunk(std::false_type{}, a1, b1);
+      if (__syncthreads_or(bad)) run_chunk(std::false_type{}, a1, b1, std::true_type{});
 #else
-      run_chunk(std::false_type{}, a1, b1);
+      run_chunk(std::false_type{}, a1, b1, std::false_type{});
 #endif
     } else {
-      run_chunk(std::false_type{}, a1, b1);
+      run_chunk(std::false_type{}, a1, b1, std::false_type{});
     }
   };
   switch (halves1) {
