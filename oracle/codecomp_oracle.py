@@ -45,6 +45,11 @@ defaults are the readings above):
     observation window; window columns get no mass;
   - pool_domain "prefix": pooling never looks across the boundary between context and window.
 
+Storage variant (not from the paper, which scores a bf16 cache): k_format "fp8_e4m3" takes the cached
+keys (and values) as 8-bit floating point codes, OCP E4M3 (1 sign, 4 exponent bits with bias 7, 3
+mantissa bits, no infinities, S.1111.111 = NaN).  A code stands for exactly the real number it encodes;
+the equations above are applied to those numbers.  A per-tensor dequantisation factor belongs in `scale`.
+
 All arrays are numpy.  bf16 inputs arrive as uint16 bit patterns and are widened exactly.
 """
 from __future__ import annotations
@@ -56,6 +61,26 @@ def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
     """Exact widening of bfloat16 bit patterns (uint16) to float64."""
     b = np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
     return b.view(np.float32).astype(np.float64)
+
+
+def fp8_e4m3_to_f64(codes: np.ndarray) -> np.ndarray:
+    """Exact value of OCP FP8 E4M3 codes (uint8): (-1)^s * 2^(e-7) * (1 + m/8) for exponent field
+    e in 1..15, (-1)^s * 2^-6 * (m/8) for e = 0 (subnormals and zero); e = 15 with m = 7 is NaN."""
+    c = np.ascontiguousarray(codes, dtype=np.uint8).astype(np.int64)
+    sign = np.where(c & 0x80, -1.0, 1.0)
+    e = (c >> 3) & 0xF
+    m = (c & 0x7).astype(np.float64)
+    normal = np.ldexp(1.0 + m / 8.0, e - 7)
+    subnormal = np.ldexp(m / 8.0, -6)
+    mag = np.where(e == 0, subnormal, normal)
+    mag = np.where((e == 15) & (m == 7), np.nan, mag)
+    return sign * mag
+
+
+def keys_to_f64(k, k_format: str = "bf16") -> np.ndarray:
+    """Cached keys as stored ("bf16": uint16 patterns, "fp8_e4m3": uint8 codes) -> the numbers they hold."""
+    assert k_format in ("bf16", "fp8_e4m3")
+    return bf16_bits_to_f64(k) if k_format == "bf16" else fp8_e4m3_to_f64(k)
 
 
 # ----------------------------------------------------------------------------------------
@@ -181,16 +206,16 @@ def gather(k: np.ndarray, v: np.ndarray, idx: np.ndarray):
 # ----------------------------------------------------------------------------------------
 
 def score_packed(q_bits, k_bits, prior, cu_seqlens, *, pool_kernel, prior_weight, scale=None,
-                 layers=None, **variant) -> np.ndarray:
-    """q_bits uint16 [L][n_seqs][H_q][W][d], k_bits uint16 [L][H_kv][T][d], prior [T],
-    cu_seqlens [n_seqs+1] -> scores float64 [L][H_kv][T].  Every (layer, request) is scored
-    on its own; layers not listed in `layers` are left as NaN."""
+                 layers=None, k_format="bf16", **variant) -> np.ndarray:
+    """q_bits uint16 [L][n_seqs][H_q][W][d], k_bits [L][H_kv][T][d] (uint16 bf16 patterns, or uint8
+    codes with k_format "fp8_e4m3"), prior [T], cu_seqlens [n_seqs+1] -> scores float64 [L][H_kv][T].
+    Every (layer, request) is scored on its own; layers not listed in `layers` are left as NaN."""
     n_layers, h_kv, total, _ = k_bits.shape
     out = np.full((n_layers, h_kv, total), np.nan, dtype=np.float64)
     for l in (range(n_layers) if layers is None else layers):
         for r in range(len(cu_seqlens) - 1):
             a, b = int(cu_seqlens[r]), int(cu_seqlens[r + 1])
-            out[l, :, a:b] = score(bf16_bits_to_f64(q_bits[l, r]), bf16_bits_to_f64(k_bits[l, :, a:b]),
+            out[l, :, a:b] = score(bf16_bits_to_f64(q_bits[l, r]), keys_to_f64(k_bits[l, :, a:b], k_format),
                                    prior[a:b], pool_kernel=pool_kernel, prior_weight=prior_weight, scale=scale,
                                    **variant)
     return out
@@ -222,10 +247,10 @@ def gather_packed(k, v, idx, cu_seqlens, cu_budgets):
 
 
 def compress_packed(q_bits, k_bits, v_bits, prior, cu_seqlens, cu_budgets, *, window, pool_kernel,
-                    prior_weight, scale=None):
+                    prior_weight, scale=None, k_format="bf16"):
     """The whole path.  Returns (scores, idx, k_out, v_out)."""
     sc = score_packed(q_bits, k_bits, prior, cu_seqlens, pool_kernel=pool_kernel,
-                      prior_weight=prior_weight, scale=scale)
+                      prior_weight=prior_weight, scale=scale, k_format=k_format)
     idx = select_packed(sc, cu_seqlens, cu_budgets, window)
     k_out, v_out = gather_packed(k_bits, v_bits, idx, cu_seqlens, cu_budgets)
     return sc, idx, k_out, v_out

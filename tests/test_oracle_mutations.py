@@ -142,3 +142,22 @@ def test_prior_sign_mutant_is_caught(monkeypatch):
     monkeypatch.setattr(orc, "fuse_prior", lambda pooled, prior, lam: pooled - lam * np.asarray(prior)[None, :])
     with pytest.raises(AssertionError):
         pins.test_prior_weight_zero_and_linearity()
+
+
+_FP8_TRUE = orc.fp8_e4m3_to_f64
+
+FP8_MUTANTS = {
+    "bias 8": lambda c: _FP8_TRUE(c) / 2,
+    "no subnormals": lambda c: np.where(((np.asarray(c) >> 3) & 0xF) == 0, 0.0, _FP8_TRUE(c)),
+    "E5M2 layout": lambda c: np.where(np.asarray(c) & 0x80, -1.0, 1.0) *
+    np.ldexp(1 + (np.asarray(c) & 3) / 4.0, ((np.asarray(c).astype(np.int64) >> 2) & 31) - 15),
+    "top exponent is infinity": lambda c: np.where(((np.asarray(c) >> 3) & 0xF) == 15, np.inf, _FP8_TRUE(c)),
+    "sign ignored": lambda c: np.abs(_FP8_TRUE(c)),
+}
+
+
+@pytest.mark.parametrize("name", sorted(FP8_MUTANTS))
+def test_fp8_decoder_mutants_are_caught(name, monkeypatch):
+    monkeypatch.setattr(orc, "fp8_e4m3_to_f64", FP8_MUTANTS[name])
+    with pytest.raises(AssertionError):
+        pins.test_fp8_e4m3_decoder_matches_library_and_format_constants()

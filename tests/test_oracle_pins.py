@@ -510,3 +510,44 @@ def test_score_variants_compose_and_default_is_unchanged():
     a = orc.select(orc.score(q, k, p, pool_kernel=3, prior_weight=0.0), w, 9)
     b_ = orc.select(orc.score(q, k, p, pool_kernel=3, prior_weight=0.0, group_reduce="sum"), w, 9)
     np.testing.assert_array_equal(a, b_)
+
+
+# ------------------------------------------------------------------ fp8 (E4M3) key storage
+
+def test_fp8_e4m3_decoder_matches_library_and_format_constants():
+    codes = np.arange(256, dtype=np.uint8)
+    ours = orc.fp8_e4m3_to_f64(codes)
+    ref = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(np.isnan(ours), np.isnan(ref)) and np.isnan(ours).sum() == 2      # 0x7f and 0xff only
+    ok = ~np.isnan(ref)
+    assert np.array_equal(ours[ok], ref[ok])
+    # constants of the format: one, largest finite, smallest subnormal, smallest normal, signed zero
+    assert ours[0x38] == 1.0 and ours[0x7E] == 448.0 and ours[0x01] == 2.0 ** -9 and ours[0x08] == 2.0 ** -6
+    assert ours[0x00] == 0.0 and ours[0x80] == 0.0 and np.signbit(ours[0x80])
+    assert ours[0x3C] == 1.5 and ours[0xC0] == -2.0
+    # magnitudes grow with the code, and the sign bit only flips the sign
+    assert (np.diff(ours[:0x7F]) > 0).all()
+    assert np.array_equal(ours[0x80:0xFF], -ours[0x00:0x7F])
+
+
+def test_fp8_keys_score_like_the_bf16_keys_holding_the_same_numbers():
+    g = np.random.default_rng(11)
+    l, hq, hkv, w, d = 2, 4, 2, 3, 8
+    cu = np.array([0, 9, 20])
+    codes = g.integers(0, 256, size=(l, hkv, 20, d)).astype(np.uint8)
+    codes[(codes & 0x7F) == 0x7F] = 0x38                       # no NaN codes
+    codes &= 0xBF                                              # magnitudes below 2: tame logits
+    # every E4M3 number is a bf16 number: the same values as bf16 patterns, built with the library cast
+    as_bf16 = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    q = g.integers(0x3C00, 0x4000, size=(l, 2, hq, w, d)).astype(np.uint16)
+    prior = g.random(20)
+    a = orc.score_packed(q, codes, prior, cu, pool_kernel=3, prior_weight=0.5, k_format="fp8_e4m3")
+    b = orc.score_packed(q, as_bf16, prior, cu, pool_kernel=3, prior_weight=0.5)
+    np.testing.assert_array_equal(a, b)
+    # and the whole path copies the codes themselves
+    cb = np.array([0, 5, 12])
+    sc, idx, ko, vo = orc.compress_packed(q, codes, codes[::-1].copy(), prior, cu, cb, window=w, pool_kernel=3,
+                                          prior_weight=0.5, k_format="fp8_e4m3")
+    assert ko.dtype == np.uint8 and np.array_equal(sc, a)
+    assert np.array_equal(ko[1, 0, 5:], codes[1, 0, 9:][idx[1, 0, 5:]])
+    assert np.array_equal(vo[0, 1, :5], codes[1, 1, :9][idx[0, 1, :5]])
