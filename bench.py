@@ -24,17 +24,17 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 
-def algorithmic_bytes(w) -> dict:
+def algorithmic_bytes(w, kv_bytes: int = 2) -> dict:
     """Bytes the method itself must move per step: K once, Q, prior, scores written and read once,
-    indices written and read once, retained K and V rows read and written."""
+    indices written and read once, retained K and V rows read and written (kv_bytes per cache element)."""
     L, H, T, TB, d = w.n_layers, w.n_kv_heads, w.total_tokens, w.total_budget, w.head_dim
     b = {
-        "k_read": L * H * T * d * 2,
+        "k_read": L * H * T * d * kv_bytes,
         "q_read": L * w.n_seqs * w.n_q_heads * w.window * d * 2,
         "prior_read": L * T * 4,
         "scores_rw": 2 * L * H * T * 4,
         "idx_rw": 2 * L * H * TB * 4,
-        "gather_rw": 2 * 2 * L * H * TB * d * 2,
+        "gather_rw": 2 * 2 * L * H * TB * d * kv_bytes,
     }
     b["total"] = sum(b.values())
     return b
@@ -64,6 +64,8 @@ def main() -> int:
                     help="timed steps; the bracketing synchronisation costs a fixed ~1.5 ms, so few steps overstate the step time")
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="qwen7b_32k")
+    ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8_e4m3"],
+                    help="storage type of the KV cache (the headline workload is bf16; fp8_e4m3 is the 8-bit variant)")
     ap.add_argument("--cpu-layers", type=int, default=28, help="layers the CPU oracle is timed and compared on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (experiments only)")
@@ -96,6 +98,8 @@ def main() -> int:
         w = wl.scaled(w, name=f"{w.name}_L{args.layers}", n_layers=args.layers)
     t0 = time.time()
     q, k, v, prior = wl.make_all(w, threads=min(16, os.cpu_count() or 8))
+    if args.kv_dtype == "fp8_e4m3":
+        k, v = wl.bf16_bits_to_fp8_codes(k), wl.bf16_bits_to_fp8_codes(v)
     t_gen = time.time() - t0
     prob = binding.DeviceProblem(w, q, k, v, prior)
     torch.cuda.synchronize()
@@ -132,7 +136,7 @@ def main() -> int:
 
     T, L = w.total_tokens, w.n_layers
     value = T * L / (ms_per_step * 1e-3)
-    ab = algorithmic_bytes(w)
+    ab = algorithmic_bytes(w, 1 if args.kv_dtype == "fp8_e4m3" else 2)
     hbm_gbs = ab["total"] / (ms_per_step * 1e-3) / 1e9
 
     # dominant kernel: one of the two MFMA passes; flops of one launch = 2 * R * sum(N_r) * d per (layer, KV head)
@@ -150,7 +154,7 @@ def main() -> int:
         "value": round(value, 1), "unit": "token-layers/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "n_layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+        "config": {"workload": w.name if args.kv_dtype == "bf16" else f"{w.name} with an {args.kv_dtype} cache", "n_layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "tokens": T, "n_seqs": w.n_seqs, "window": w.window,
                    "budget_total": w.total_budget, "pool_kernel": w.pool_kernel, "prior_weight": w.prior_weight},
         "tokens_per_s_whole_model": round(T / (ms_per_step * 1e-3), 1),
@@ -176,7 +180,7 @@ def main() -> int:
         t0 = time.perf_counter()
         sc_ref, idx_ref, ko_ref, vo_ref = orc.compress_packed(q[layers], k[layers], v[layers], prior, cu, cb,
                                                              window=w.window, pool_kernel=w.pool_kernel,
-                                                             prior_weight=w.prior_weight)
+                                                             prior_weight=w.prior_weight, k_format=args.kv_dtype)
         t_cpu = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(T * len(layers) / t_cpu, 1), "unit": "token-layers/s", "cores": cores,
                                "kind": "oracle", "seconds": round(t_cpu, 2),

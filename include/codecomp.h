@@ -23,7 +23,7 @@
  *     towards B_r, so W <= B_r <= N_r).  T = cu_seqlens[n_seqs], TB = cu_budgets[n_seqs].
  *   - Layouts (innermost dimension contiguous; a stride of 0 selects the dense default):
  *       q_obs  bf16 [n_layers][n_seqs][n_q_heads][W][d]
- *       k, v   bf16 [n_layers][n_kv_heads][T][d]
+ *       k, v   bf16 [n_layers][n_kv_heads][T][d]        (or FP8 codes, see kv_dtype)
  *       prior  f32  [T]                      (one value per token, shared by layers and heads,
  *                                             finite and >= 0)
  *       scores f32  [n_layers][n_kv_heads][T]          (dense)
@@ -58,7 +58,7 @@ enum {
   CODECOMP_EINVAL_SEQLENS = -8,   /* cu_seqlens / cu_budgets not starting at 0 or not increasing  */
   CODECOMP_EINVAL_WORKSPACE = -9, /* workspace NULL, misaligned (256 B) or too small              */
   CODECOMP_EINVAL_PRIOR = -10,    /* prior_weight negative or not finite; softmax_scale < 0       */
-  CODECOMP_EINVAL_MODE = -11      /* select_mode / score_variant unknown or unsupported for the shape, bad span budget */
+  CODECOMP_EINVAL_MODE = -11      /* select_mode / score_variant / kv_dtype unknown or unsupported for the shape, bad span budget */
 };
 
 typedef struct codecomp_params {
@@ -85,7 +85,7 @@ typedef struct codecomp_params {
   float span_budget_ratio;     /* rho_span in [0, 1]                                              */
   int32_t span_budget_min;     /* B_min >= 0                                                      */
   int32_t score_variant;       /* bit flags CODECOMP_VARIANT_*; 0 = the default readings          */
-  int32_t reserved;            /* must be 0                                                       */
+  int32_t kv_dtype;            /* CODECOMP_KV_BF16 (0) or CODECOMP_KV_FP8_E4M3 (1): element type of k, v, k_out, v_out */
 } codecomp_params;
 
 /* Other readings of what the paper leaves open about the tail of the score step (section
@@ -105,6 +105,15 @@ enum {
   CODECOMP_VARIANT_SOFTMAX_PREFIX = 8,
   CODECOMP_VARIANT_POOL_PREFIX = 16
 };
+
+/* Storage type of the KV cache (k, v and the compact k_out, v_out; q_obs is always bf16).  Not from the paper,
+ * whose caches are 16-bit: serving stacks also keep the cache as 8-bit floating point.
+ *   FP8_E4M3: one byte per element, OCP E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinity,
+ *   S.1111.111 = NaN).  A key element counts as exactly the number its code encodes (the kernels widen it
+ *   to bf16, which holds every E4M3 number, so the logits are the same as for that bf16 cache); a per-tensor
+ *   dequantisation factor is folded into softmax_scale by the caller.  Strides stay in elements (= bytes) and
+ *   the kv / out strides must be multiples of 16.  The gather copies codes bit for bit. */
+enum { CODECOMP_KV_BF16 = 0, CODECOMP_KV_FP8_E4M3 = 1 };
 
 /* How the structural prior enters the selection.
  * ADDITIVE : scores = pooled attention + lambda * prior, one top-(B - W) over them.

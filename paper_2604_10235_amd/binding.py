@@ -37,7 +37,7 @@ class codecomp_params(C.Structure):
         ("kv_stride_layer", C.c_int64), ("kv_stride_head", C.c_int64), ("kv_stride_tok", C.c_int64),
         ("out_stride_layer", C.c_int64), ("out_stride_head", C.c_int64), ("out_stride_tok", C.c_int64),
         ("span_budget_ratio", C.c_float), ("span_budget_min", C.c_int32),
-        ("score_variant", C.c_int32), ("reserved", C.c_int32),
+        ("score_variant", C.c_int32), ("kv_dtype", C.c_int32),
     ]
 
 
@@ -163,6 +163,7 @@ def codecomp_score(q_obs, k, prior, params, scores, workspace) -> None:
 
 STAGE_ROW_STATS, STAGE_ROW_MERGE, STAGE_MASS, STAGE_FINISH, STAGE_ALL = 1, 2, 4, 8, 15
 VARIANT_GROUP_SUM, VARIANT_GROUP_MAX, VARIANT_POOL_MAX, VARIANT_SOFTMAX_PREFIX, VARIANT_POOL_PREFIX = 1, 2, 4, 8, 16
+KV_BF16, KV_FP8_E4M3 = 0, 1
 
 
 def codecomp_score_stages(q_obs, k, prior, params, scores, workspace, stages: int) -> None:
@@ -224,7 +225,8 @@ def codecomp_chunk_budgets(sigma, chunk_len, *, ratio, m_min, m_max, r_max, eps,
 
 class DeviceProblem:
     """Device buffers of one workload: inputs uploaded from the host arrays of the workload
-    generator, outputs and workspace allocated with torch.  Plumbing only."""
+    generator, outputs and workspace allocated with torch.  Plumbing only.  k_bits / v_bits of dtype
+    uint8 are an FP8 E4M3 cache (kv_dtype = KV_FP8_E4M3), uint16 a bf16 one."""
 
     def __init__(self, w, q_bits: np.ndarray, k_bits: np.ndarray, v_bits: Optional[np.ndarray], prior: np.ndarray,
                  device: str = "cuda:0", select_mode: int = 0, span_budget_ratio: float = 0.5,
@@ -236,9 +238,16 @@ class DeviceProblem:
         def up_bits(x):
             return torch.from_numpy(x.view(np.int16)).to(dev).view(torch.bfloat16)
 
+        fp8 = k_bits.dtype == np.uint8
+        if v_bits is not None and v_bits.dtype != k_bits.dtype:
+            raise ValueError("k and v must have the same storage type")
+
+        def up_kv(x):
+            return torch.from_numpy(x).to(dev) if fp8 else up_bits(x)
+
         self.q = up_bits(q_bits)
-        self.k = up_bits(k_bits)
-        self.v = up_bits(v_bits) if v_bits is not None else None
+        self.k = up_kv(k_bits)
+        self.v = up_kv(v_bits) if v_bits is not None else None
         self.prior = torch.from_numpy(prior).to(dev)
         self.n_layers = int(k_bits.shape[0])
         self.cu_seqlens = torch.from_numpy(w.cu_seqlens()).to(dev)
@@ -249,13 +258,14 @@ class DeviceProblem:
                                   cu_budgets_host=w.cu_budgets(), cu_seqlens_dev=_ptr(self.cu_seqlens),
                                   cu_budgets_dev=_ptr(self.cu_budgets), select_mode=select_mode,
                                   span_budget_ratio=span_budget_ratio, span_budget_min=span_budget_min,
-                                  score_variant=score_variant)
+                                  score_variant=score_variant, kv_dtype=KV_FP8_E4M3 if fp8 else KV_BF16)
         rc = codecomp_validate(self.params)
         _check(rc, "codecomp_validate")
         T, TB = w.total_tokens, w.total_budget
         self.scores = torch.empty((self.n_layers, w.n_kv_heads, T), dtype=torch.float32, device=dev)
         self.idx = torch.empty((self.n_layers, w.n_kv_heads, TB), dtype=torch.int32, device=dev)
-        self.k_out = torch.empty((self.n_layers, w.n_kv_heads, TB, w.head_dim), dtype=torch.bfloat16, device=dev)
+        self.k_out = torch.empty((self.n_layers, w.n_kv_heads, TB, w.head_dim),
+                                 dtype=torch.uint8 if fp8 else torch.bfloat16, device=dev)
         self.v_out = torch.empty_like(self.k_out)
         self.workspace = torch.empty(max(256, codecomp_workspace_bytes(self.params)), dtype=torch.uint8, device=dev)
 
@@ -280,6 +290,8 @@ class DeviceProblem:
 
     @staticmethod
     def bits(t) -> np.ndarray:
-        """bf16 tensor -> host uint16 bit patterns."""
+        """bf16 tensor -> host uint16 bit patterns (a uint8 tensor of FP8 codes comes back as it is)."""
         import torch
+        if t.dtype == torch.uint8:
+            return t.cpu().numpy()
         return t.view(torch.int16).cpu().numpy().view(np.uint16)

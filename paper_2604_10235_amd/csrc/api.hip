@@ -66,7 +66,8 @@ int make_plan(const codecomp_params* p, Plan* pl) {
     return CODECOMP_EINVAL_MODE;
   constexpr int kKnownVariants = CODECOMP_VARIANT_GROUP_SUM | CODECOMP_VARIANT_GROUP_MAX | CODECOMP_VARIANT_POOL_MAX |
                                  CODECOMP_VARIANT_SOFTMAX_PREFIX | CODECOMP_VARIANT_POOL_PREFIX;
-  if ((p->score_variant & ~kKnownVariants) != 0 || p->reserved != 0) return CODECOMP_EINVAL_MODE;
+  if ((p->score_variant & ~kKnownVariants) != 0) return CODECOMP_EINVAL_MODE;
+  if (p->kv_dtype != CODECOMP_KV_BF16 && p->kv_dtype != CODECOMP_KV_FP8_E4M3) return CODECOMP_EINVAL_MODE;
   if ((p->score_variant & CODECOMP_VARIANT_GROUP_SUM) && (p->score_variant & CODECOMP_VARIANT_GROUP_MAX)) return CODECOMP_EINVAL_MODE;
   if ((int64_t)p->n_layers * p->n_kv_heads > 65535) return CODECOMP_EINVAL_SHAPE;   // one grid axis
   if (p->n_kv_heads < 1 || p->n_q_heads < 1 || p->n_q_heads % p->n_kv_heads != 0) return CODECOMP_EINVAL_HEADS;
@@ -92,11 +93,15 @@ int make_plan(const codecomp_params* p, Plan* pl) {
                              p->out_stride_layer, p->out_stride_head, p->out_stride_tok};
   for (int64_t s : strides)
     if (s < 0 || s % 8 != 0) return CODECOMP_EINVAL_SHAPE;   // rows are moved as 16-byte pieces
+  if (p->kv_dtype == CODECOMP_KV_FP8_E4M3)                   // ... which hold 16 one-byte elements
+    for (int i = 4; i < 10; ++i)
+      if (strides[i] % 16 != 0) return CODECOMP_EINVAL_SHAPE;
 
   pl->L = p->n_layers; pl->Hq = p->n_q_heads; pl->Hkv = p->n_kv_heads; pl->G = pl->Hq / pl->Hkv;
   pl->d = p->head_dim; pl->W = p->window; pl->pool = p->pool_kernel; pl->n_seqs = p->n_seqs;
   pl->select_mode = p->select_mode;
   pl->variant = p->score_variant;
+  pl->kv_fp8 = p->kv_dtype == CODECOMP_KV_FP8_E4M3 ? 1 : 0;
   pl->key_trim = (p->score_variant & CODECOMP_VARIANT_SOFTMAX_PREFIX) ? p->window : 0;
   pl->span_ratio = p->span_budget_ratio; pl->span_min = p->span_budget_min;
   // two-stage selection keeps the prior out of the scores: structure is handled by the selection itself

@@ -1,21 +1,21 @@
 // Gather step: copy the retained K and V rows into the compact per-layer cache (the
 // compressed chunk of section "Position Encoding": rows keep their original order).
-// Pure data movement: a row of d bf16 values is moved as d/8 16-byte pieces by consecutive
-// lanes, so both the reads and the writes of a row are one contiguous segment.
+// Pure data movement: a row of d elements (bf16, or one-byte FP8 codes) is moved as 16-byte pieces
+// by consecutive lanes, so both the reads and the writes of a row are one contiguous segment.
 #include "plan.h"
 
 namespace codecomp {
 
 struct GatherArgs {
-  const uint16_t* k;
-  const uint16_t* v;
+  const unsigned char* k;
+  const unsigned char* v;
   const int32_t* idx;
   const int32_t* cu_seqlens;
   const int32_t* cu_budgets;
-  uint16_t* k_out;
-  uint16_t* v_out;
-  int n_seqs, Hkv, TB, pieces_log2;    // pieces per row = d / 8 (8 or 16)
-  int64_t kv_sl, kv_sh, kv_st, o_sl, o_sh, o_st;
+  unsigned char* k_out;
+  unsigned char* v_out;
+  int n_seqs, Hkv, TB, pieces_log2;    // 16-byte pieces per row = d * element size / 16 (4, 8 or 16)
+  int64_t kv_sl, kv_sh, kv_st, o_sl, o_sh, o_st;     // in bytes
 };
 
 #ifndef CODECOMP_GATHER_ROWS
@@ -28,14 +28,14 @@ constexpr int kGatherThreads = 256;
 constexpr int kGatherRowsPerThread = CODECOMP_GATHER_ROWS;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ u32x4 ld16(const uint16_t* p) {
+__device__ __forceinline__ u32x4 ld16(const unsigned char* p) {
 #if CODECOMP_GATHER_NT
   return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
 #else
   return *reinterpret_cast<const u32x4*>(p);
 #endif
 }
-__device__ __forceinline__ void st16(uint16_t* p, u32x4 v) {
+__device__ __forceinline__ void st16(unsigned char* p, u32x4 v) {
 #if CODECOMP_GATHER_NT
   __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
 #else
@@ -51,10 +51,10 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
   const int lz = blockIdx.y;
   const int layer = lz / a.Hkv, head = lz - layer * a.Hkv;
   const int32_t* idx = a.idx + (int64_t)lz * a.TB;
-  const uint16_t* kb = a.k + layer * a.kv_sl + head * a.kv_sh;
-  const uint16_t* vb = a.v + layer * a.kv_sl + head * a.kv_sh;
-  uint16_t* ko = a.k_out + layer * a.o_sl + head * a.o_sh;
-  uint16_t* vo = a.v_out + layer * a.o_sl + head * a.o_sh;
+  const unsigned char* kb = a.k + layer * a.kv_sl + head * a.kv_sh;
+  const unsigned char* vb = a.v + layer * a.kv_sl + head * a.kv_sh;
+  unsigned char* ko = a.k_out + layer * a.o_sl + head * a.o_sh;
+  unsigned char* vo = a.v_out + layer * a.o_sl + head * a.o_sh;
   const int slot0 = blockIdx.x * rows_per_pass * kGatherRowsPerThread + rsub;
 
   u32x4 kv[kGatherRowsPerThread], vv[kGatherRowsPerThread];
@@ -70,16 +70,16 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
       // indices are clamped into the request so that a corrupt idx can never read out of bounds
       const int s0 = a.cu_seqlens[lo], n = a.cu_seqlens[lo + 1] - s0;
       const int64_t tok = (int64_t)s0 + min(max(idx[slot], 0), n - 1);
-      kv[i] = ld16(kb + tok * a.kv_st + piece * 8);
-      vv[i] = ld16(vb + tok * a.kv_st + piece * 8);
+      kv[i] = ld16(kb + tok * a.kv_st + piece * 16);
+      vv[i] = ld16(vb + tok * a.kv_st + piece * 16);
     }
   }
 #pragma unroll
   for (int i = 0; i < kGatherRowsPerThread; ++i) {
     const int slot = slot0 + i * rows_per_pass;
     if (slot < a.TB) {
-      st16(ko + (int64_t)slot * a.o_st + piece * 8, kv[i]);
-      st16(vo + (int64_t)slot * a.o_st + piece * 8, vv[i]);
+      st16(ko + (int64_t)slot * a.o_st + piece * 16, kv[i]);
+      st16(vo + (int64_t)slot * a.o_st + piece * 16, vv[i]);
     }
   }
 }
@@ -87,12 +87,14 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
 int launch_gather(const Plan& pl, const void* k, const void* v, const int32_t* idx, void* k_out, void* v_out,
                   hipStream_t stream) {
   GatherArgs a;
-  a.k = static_cast<const uint16_t*>(k); a.v = static_cast<const uint16_t*>(v); a.idx = idx;
+  a.k = static_cast<const unsigned char*>(k); a.v = static_cast<const unsigned char*>(v); a.idx = idx;
   a.cu_seqlens = pl.cu_seqlens_dev; a.cu_budgets = pl.cu_budgets_dev;
-  a.k_out = static_cast<uint16_t*>(k_out); a.v_out = static_cast<uint16_t*>(v_out);
-  a.n_seqs = pl.n_seqs; a.Hkv = pl.Hkv; a.TB = pl.TB; a.pieces_log2 = pl.d == 128 ? 4 : 3;
-  a.kv_sl = pl.kv_sl; a.kv_sh = pl.kv_sh; a.kv_st = pl.kv_st;
-  a.o_sl = pl.o_sl; a.o_sh = pl.o_sh; a.o_st = pl.o_st;
+  a.k_out = static_cast<unsigned char*>(k_out); a.v_out = static_cast<unsigned char*>(v_out);
+  const int esz = pl.kv_fp8 ? 1 : 2;
+  a.n_seqs = pl.n_seqs; a.Hkv = pl.Hkv; a.TB = pl.TB;
+  a.pieces_log2 = (pl.d == 128 ? 4 : 3) - (pl.kv_fp8 ? 1 : 0);
+  a.kv_sl = pl.kv_sl * esz; a.kv_sh = pl.kv_sh * esz; a.kv_st = pl.kv_st * esz;
+  a.o_sl = pl.o_sl * esz; a.o_sh = pl.o_sh * esz; a.o_st = pl.o_st * esz;
   const int rows_per_block = (kGatherThreads >> a.pieces_log2) * kGatherRowsPerThread;
   gather_kernel<<<dim3((pl.TB + rows_per_block - 1) / rows_per_block, pl.L * pl.Hkv), dim3(kGatherThreads), 0,
                   stream>>>(a);

@@ -22,6 +22,7 @@ struct Plan {
   int select_mode;           // CODECOMP_SELECT_*
   int variant;               // CODECOMP_VARIANT_* flags
   int key_trim;              // keys at the end of every request that the softmax leaves out (W or 0)
+  int kv_fp8;                // 1: k, v and the compact cache hold one FP8 E4M3 code per element (else bf16)
   float span_ratio; int span_min;
   int T, TB;                 // total tokens / total output slots over the packed requests
   int max_n;                 // longest request

@@ -30,10 +30,12 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 // 16-byte register quantum for loads/stores and MFMA fragments (a native vector: plain loads, no struct copies)
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 struct ScoreArgs {
   const uint16_t* q;
-  const uint16_t* k;
+  const unsigned char* k;   // keys: bf16 patterns, or one FP8 E4M3 code per element (strides stay in elements)
   const int32_t* cu_seqlens;
   float* stats;   // [segment slot][waves*64][2] : (max * c, sum of exp2(s*c - max*c)) per wave slot row
   float* lse;     // [L*Hkv][n_seqs][lrows]         : log2 sum_j exp2(s_j * c), lrows = row_splits * nb * 32
@@ -68,6 +70,20 @@ __device__ unsigned char g_simd[2048][8];     // SIMD id of each wave of a workg
 #endif
 
 __device__ __forceinline__ bf16x8 frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// What goes into the LDS tile for one staged piece of 8 key elements: bf16 as it is; 8 FP8 E4M3 codes widened to
+// bf16.  Every E4M3 number is a bf16 number, so the conversion to f32 followed by dropping the low 16 bits is exact.
+__device__ __forceinline__ u32x4 to_bf16x8(u32x4 v) { return v; }
+__device__ __forceinline__ u32x4 to_bf16x8(u32x2 v) {
+  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)v.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)v.x, true);
+  const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)v.y, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)v.y, true);
+  u32x4 r;      // v_perm: bytes 2,3 of the second operand, then bytes 2,3 of the first
+  r.x = __builtin_amdgcn_perm(__float_as_uint(a.y), __float_as_uint(a.x), 0x07060302u);
+  r.y = __builtin_amdgcn_perm(__float_as_uint(b.y), __float_as_uint(b.x), 0x07060302u);
+  r.z = __builtin_amdgcn_perm(__float_as_uint(c.y), __float_as_uint(c.x), 0x07060302u);
+  r.w = __builtin_amdgcn_perm(__float_as_uint(d.y), __float_as_uint(d.x), 0x07060302u);
+  return r;
+}
 
 // Request that holds position `xr` of a (layer*head, row split) sequence; tile_in_seq < 0 inside the lead.
 __device__ __forceinline__ void locate_tile(const int32_t* cu, int n_seqs, int lead, int trim, int xr, int& seq, int& tok0,
@@ -104,13 +120,16 @@ __device__ __forceinline__ f32x16 mma_step(u32x4 qfrag, u32x4 kfrag, f32x16 acc)
 }
 
 // GMAX (pass 2 only): the largest query-head mass of the group instead of the (scaled) sum over its heads.
-template <int D, int NW, int PASS, bool GMAX = false>
+// K8: the keys are FP8 E4M3 codes; they are widened to bf16 on their way into LDS, everything after is the same.
+template <int D, int NW, int PASS, bool GMAX = false, bool K8 = false>
 __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(ScoreArgs a) {
   static_assert(PASS == 2 || !GMAX, "the group reduction happens in pass 2");
   constexpr int NT = NW * 64;
   constexpr int KS = D / 16;                   // MFMA k-steps per logit
   constexpr int ROWB = D * 2 + 16;             // LDS bytes per key row (+16: spreads rows over banks)
-  constexpr int CH_PER_ROW = D / 8;            // 16-byte pieces per key row
+  constexpr int CH_PER_ROW = D / 8;            // pieces of 8 elements per key row (16 bytes in LDS)
+  constexpr int ESZ = K8 ? 1 : 2;              // bytes per stored key element
+  using stage_t = std::conditional_t<K8, u32x2, u32x4>;   // one piece as loaded
   constexpr int NCH = kTileKeys * CH_PER_ROW;  // pieces per tile
   constexpr int LD = (NCH + NT - 1) / NT;      // pieces staged per thread
   constexpr int LDS_ROWS = LD * NT / CH_PER_ROW;   // >= kTileKeys: rows past the tile are staging slack, never read
@@ -168,7 +187,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 
   // ---- K tile staging: global -> registers -> LDS.  Rows past the end of the chunk re-read its
   // last key (always in bounds); such columns are masked (pass 1) or never stored (pass 2).
-  const uint16_t* kb = a.k + (int64_t)layer * a.kv_sl + (int64_t)head * a.kv_sh + (int64_t)tok0 * a.kv_st;
+  const unsigned char* kb = a.k + ((int64_t)layer * a.kv_sl + (int64_t)head * a.kv_sh + (int64_t)tok0 * a.kv_st) * ESZ;
   // Workgroups that have a compute unit to themselves (more than four waves) keep two tiles in flight in two
   // register sets in pass 2: with nothing else resident, a tile that arrives late stalls every SIMD of
   // the unit.  (Measured: 4% off pass 2, nothing off pass 1, whose loop is the shorter one.)
@@ -177,12 +196,12 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 #else
   constexpr bool DEEP = NW > 4 && PASS == 2;
 #endif
-  u32x4 stage[LD];
-  u32x4 stage2[DEEP ? LD : 1];
-  // byte offset of this thread's first 16-byte piece inside a tile; its i-th piece is NT / CH_PER_ROW rows further
+  stage_t stage[LD];
+  stage_t stage2[DEEP ? LD : 1];
+  // byte offset of this thread's first piece inside a tile; its i-th piece is NT / CH_PER_ROW rows further
   static_assert(NT % CH_PER_ROW == 0, "pieces of one thread share a column");
-  const uint32_t soff0 = (uint32_t)((tid / CH_PER_ROW) * (int)a.kv_st + (tid % CH_PER_ROW) * 8) * 2u;
-  const uint32_t sstep = (uint32_t)((NT / CH_PER_ROW) * (int)a.kv_st) * 2u;
+  const uint32_t soff0 = (uint32_t)((tid / CH_PER_ROW) * (int)a.kv_st + (tid % CH_PER_ROW) * 8) * (uint32_t)ESZ;
+  const uint32_t sstep = (uint32_t)((NT / CH_PER_ROW) * (int)a.kv_st) * (uint32_t)ESZ;
   // fast path: every staged row (slack rows included) lies inside the chunk -> uniform base + lane offset
 #ifdef CODECOMP_EXP_NEAR_GLOAD   /* experiment: always re-read the first tile of the segment (cache hits) */
 #define CODECOMP_KEY0(X) (((X) & 0) + kstart)
@@ -193,15 +212,15 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   {                                                                                                 \
     const int key0_ = CODECOMP_KEY0(KEY0);                                                          \
     if (key0_ + LDS_ROWS <= kend) {                                                                 \
-      const char* tb_ = reinterpret_cast<const char*>(kb + (int64_t)key0_ * a.kv_st);               \
+      const unsigned char* tb_ = kb + (int64_t)key0_ * a.kv_st * ESZ;                              \
       _Pragma("unroll") for (int i = 0; i < LD; ++i)                                                \
-        ST[i] = *reinterpret_cast<const u32x4*>(tb_ + (size_t)i * sstep + soff0);                   \
+        ST[i] = *reinterpret_cast<const stage_t*>(tb_ + (size_t)i * sstep + soff0);                 \
     } else {                                                                                        \
       _Pragma("unroll") for (int i = 0; i < LD; ++i) {                                              \
         const int cidx = tid + i * NT;                                                              \
         const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;                           \
         const int key = min(key0_ + row, kend - 1);                                                 \
-        ST[i] = *reinterpret_cast<const u32x4*>(kb + (int64_t)key * a.kv_st + col * 8);             \
+        ST[i] = *reinterpret_cast<const stage_t*>(kb + ((int64_t)key * a.kv_st + col * 8) * ESZ);   \
       }                                                                                             \
     }                                                                                               \
   }
@@ -209,7 +228,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   _Pragma("unroll") for (int i = 0; i < LD; ++i) {                                                  \
     const int cidx = tid + i * NT;                                                                  \
     const int row = cidx / CH_PER_ROW, col = cidx - row * CH_PER_ROW;                               \
-    *reinterpret_cast<u32x4*>(&ktile[BUF][row * ROWB + col * 16]) = ST[i];                          \
+    *reinterpret_cast<u32x4*>(&ktile[BUF][row * ROWB + col * 16]) = to_bf16x8(ST[i]);               \
   }
 
   // The first K tile of the segment is sent for before the query rows, so that both arrive in one round trip.
@@ -755,16 +774,16 @@ static int score_grid(const Plan& pl, int resident) {
   return g < 1 ? 1 : g;
 }
 
-template <int D, int NW>
+template <int D, int NW, bool K8>
 static int launch_passes(const Plan& pl, ScoreArgs a, hipStream_t stream, unsigned stages) {
-  static const int resident1 = resident_workgroups(score_pass_kernel<D, NW, 1>, NW * 64);
-  static const int resident2 = resident_workgroups(score_pass_kernel<D, NW, 2>, NW * 64);
-  static const int resident2m = resident_workgroups(score_pass_kernel<D, NW, 2, true>, NW * 64);
+  static const int resident1 = resident_workgroups(score_pass_kernel<D, NW, 1, false, K8>, NW * 64);
+  static const int resident2 = resident_workgroups(score_pass_kernel<D, NW, 2, false, K8>, NW * 64);
+  static const int resident2m = resident_workgroups(score_pass_kernel<D, NW, 2, true, K8>, NW * 64);
   const dim3 block(NW * 64);
   a.stat_wgs = score_grid(pl, resident1);
   const bool any_tile = pl.real_tiles > 0;      // false: prefix-only softmax with no prefix anywhere
   if ((stages & CODECOMP_STAGE_ROW_STATS) && any_tile) {
-    score_pass_kernel<D, NW, 1><<<dim3(a.stat_wgs), block, 0, stream>>>(a);
+    score_pass_kernel<D, NW, 1, false, K8><<<dim3(a.stat_wgs), block, 0, stream>>>(a);
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
   if (stages & CODECOMP_STAGE_ROW_MERGE) {
@@ -774,22 +793,22 @@ static int launch_passes(const Plan& pl, ScoreArgs a, hipStream_t stream, unsign
   }
   if ((stages & CODECOMP_STAGE_MASS) && any_tile) {
     if (pl.variant & CODECOMP_VARIANT_GROUP_MAX)
-      score_pass_kernel<D, NW, 2, true><<<dim3(score_grid(pl, resident2m)), block, 0, stream>>>(a);
+      score_pass_kernel<D, NW, 2, true, K8><<<dim3(score_grid(pl, resident2m)), block, 0, stream>>>(a);
     else
-      score_pass_kernel<D, NW, 2><<<dim3(score_grid(pl, resident2)), block, 0, stream>>>(a);
+      score_pass_kernel<D, NW, 2, false, K8><<<dim3(score_grid(pl, resident2)), block, 0, stream>>>(a);
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
   return 0;
 }
 
-template <int D>
+template <int D, bool K8>
 static int dispatch_waves(const Plan& pl, const ScoreArgs& a, hipStream_t s, unsigned st) {
   switch (pl.waves) {
-    case 1: return launch_passes<D, 1>(pl, a, s, st);
-    case 2: return launch_passes<D, 2>(pl, a, s, st);
-    case 3: return launch_passes<D, 3>(pl, a, s, st);
-    case 4: return launch_passes<D, 4>(pl, a, s, st);
-    case 8: return launch_passes<D, 8>(pl, a, s, st);
+    case 1: return launch_passes<D, 1, K8>(pl, a, s, st);
+    case 2: return launch_passes<D, 2, K8>(pl, a, s, st);
+    case 3: return launch_passes<D, 3, K8>(pl, a, s, st);
+    case 4: return launch_passes<D, 4, K8>(pl, a, s, st);
+    case 8: return launch_passes<D, 8, K8>(pl, a, s, st);
   }
   return CODECOMP_EINVAL_SHAPE;
 }
@@ -799,7 +818,7 @@ int launch_score(const Plan& pl, const void* q, const void* k, const float* prio
   char* ws = static_cast<char*>(workspace);
   ScoreArgs a;
   a.q = static_cast<const uint16_t*>(q);
-  a.k = static_cast<const uint16_t*>(k);
+  a.k = static_cast<const unsigned char*>(k);
   a.cu_seqlens = pl.cu_seqlens_dev;
   a.stats = reinterpret_cast<float*>(ws + pl.off_stats);
   a.lse = reinterpret_cast<float*>(ws + pl.off_lse);
@@ -817,7 +836,9 @@ int launch_score(const Plan& pl, const void* q, const void* k, const float* prio
   a.inv_g = (pl.variant & CODECOMP_VARIANT_GROUP_SUM) ? 1.0f : 1.0f / (float)pl.G;
   a.key_trim = pl.key_trim;
   a.blocks_per_head = (pl.variant & CODECOMP_VARIANT_GROUP_MAX) ? pl.W / 32 : 1;
-  int rc = pl.d == 128 ? dispatch_waves<128>(pl, a, stream, stages) : dispatch_waves<64>(pl, a, stream, stages);
+  int rc;
+  if (pl.kv_fp8) rc = pl.d == 128 ? dispatch_waves<128, true>(pl, a, stream, stages) : dispatch_waves<64, true>(pl, a, stream, stages);
+  else rc = pl.d == 128 ? dispatch_waves<128, false>(pl, a, stream, stages) : dispatch_waves<64, false>(pl, a, stream, stages);
   if (rc) return rc;
 #if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
   if (const char* path_ = getenv("CODECOMP_TRACE_OUT")) {

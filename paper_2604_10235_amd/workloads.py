@@ -152,6 +152,15 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     return (rounded >> np.uint32(16)).astype(np.uint16)
 
 
+def bf16_bits_to_fp8_codes(bits: np.ndarray) -> np.ndarray:
+    """An FP8 (OCP E4M3) copy of a bf16 cache, as a serving stack that keeps its KV cache in 8 bits would hold
+    it: every element rounded to the nearest E4M3 number by the library cast (magnitudes clamped to the
+    format's largest finite value, 448, first).  Returns uint8 codes of the same shape."""
+    import torch
+    x = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(torch.float32)
+    return x.clamp_(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
 def make_prior(w: Workload) -> np.ndarray:
     """Per-token prior: each request is cut into spans of uniform length in [span_min, span_max];
     a span is flagged with probability flag_rate; tokens of a flagged span get p (one draw per

@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_layout_matches_header():
-    # 10 x 4-byte fields, 4 pointers, 10 x int64 strides, span budget (float + int32), variant flags + reserved
+    # 10 x 4-byte fields, 4 pointers, 10 x int64 strides, span budget (float + int32), variant flags + kv_dtype
     assert C.sizeof(b.codecomp_params) == 40 + 32 + 80 + 8 + 8
     assert b.codecomp_params.score_variant.offset == 160
     assert b.codecomp_params.span_budget_ratio.offset == 152
@@ -90,7 +90,9 @@ def test_valid_params_and_workspace_size():
     (dict(score_variant=2), -11),                                      # group max needs window % 32 == 0 (16 here)
     (dict(score_variant=2, window=64, n_q_heads=18, cu_seqlens_host=np.array([0, 100, 300]),
           cu_budgets_host=np.array([0, 70, 140])), -11),                # group max needs all rows in one workgroup (9 * 64 > 512)
-    (dict(reserved=1), -11),
+    (dict(kv_dtype=2), -11),
+    (dict(kv_dtype=-1), -11),
+    (dict(kv_dtype=1, kv_stride_tok=136), -2),      # FP8 rows move as 16-byte pieces of 16 elements
     (dict(select_mode=1, span_budget_ratio=1.5), -11),
     (dict(select_mode=1, span_budget_ratio=0.5, span_budget_min=-1), -11),
     (dict(pool_kernel=1027), -5),

@@ -22,11 +22,14 @@ def oracle_variant(flags: int) -> dict:
                 pool_domain="prefix" if flags & 16 else "row")
 
 
-def run_case(w, *, fused=True, check_oracle=True, variant=0):
-    """Runs the three steps (or the fused call) and compares every stage with the oracle."""
+def run_case(w, *, fused=True, check_oracle=True, variant=0, kv="bf16"):
+    """Runs the three steps (or the fused call) and compares every stage with the oracle.  kv = "fp8_e4m3":
+    the cache (k and v) is the FP8 copy of the workload's bf16 cache."""
     import torch
     b = _binding()
     q, k, v, prior = wl.make_all(w)
+    if kv == "fp8_e4m3":
+        k, v = wl.bf16_bits_to_fp8_codes(k), wl.bf16_bits_to_fp8_codes(v)
     prob = b.DeviceProblem(w, q, k, v, prior, score_variant=variant)
     if fused:
         prob.compress()
@@ -48,7 +51,7 @@ def run_case(w, *, fused=True, check_oracle=True, variant=0):
         return prob, sc_gpu, idx_gpu
     # scores and index sets against the fp64 oracle
     sc_ref = orc.score_packed(q, k, prior, cu, pool_kernel=w.pool_kernel, prior_weight=w.prior_weight,
-                              **oracle_variant(variant))
+                              k_format=kv, **oracle_variant(variant))
     pu.assert_scores_close(sc_gpu, sc_ref)
     idx_ref = orc.select_packed(sc_ref, cu, cb, w.window)
     for l in range(w.n_layers):
@@ -364,3 +367,65 @@ def test_compress_replays_from_a_hip_graph():
         for got, want in zip((prob.scores, prob.idx, prob.k_out, prob.v_out), ref):
             assert torch.equal(got.view(torch.uint8) if got.dtype == torch.bfloat16 else got,
                                want.view(torch.uint8) if want.dtype == torch.bfloat16 else want)
+
+
+# ------------------------------------------------------------------ FP8 (E4M3) cache
+
+def test_fp8_cache_tiny_and_ragged():
+    run_case(wl.tiny(), fused=False, kv="fp8_e4m3")
+    run_case(wl.tiny(), fused=True, kv="fp8_e4m3")
+    w = wl.scaled(wl.ragged_agentic(), seqlens=[700, 1300, 64, 2049, 1024, 65], budgets=[70, 130, 64, 204, 1024, 65])
+    run_case(w, kv="fp8_e4m3")
+
+
+def test_fp8_cache_model_shapes():
+    """Eight waves with shared row blocks (448 rows), a ragged last tile, head_dim 128; four waves; two row splits."""
+    run_case(wl.scaled(wl.qwen7b_32k(), n_layers=2, seqlens=[5000]), kv="fp8_e4m3")
+    run_case(wl.scaled(wl.llama8b_64k(), n_layers=2, seqlens=[3001], n_q_heads=8, n_kv_heads=2), kv="fp8_e4m3")
+    run_case(wl.scaled(wl.long_128k(), n_layers=1, seqlens=[4100], n_kv_heads=2, n_q_heads=14), kv="fp8_e4m3")
+
+
+@pytest.mark.parametrize("variant", [2, 1 | 4 | 8 | 16])
+def test_fp8_cache_with_score_variants(variant):
+    w = wl.scaled(wl.qwen7b_32k(), n_layers=1, seqlens=[1500, 64, 700], budgets=[150, 64, 90], n_kv_heads=2, n_q_heads=14)
+    run_case(w, variant=variant, kv="fp8_e4m3")
+
+
+@pytest.mark.parametrize("band", range(8))
+def test_fp8_every_code_is_read_as_its_value(band):
+    """Keys drawn from 16 neighbouring magnitude codes (both signs) at a time, from the subnormals up to 448, with
+    the queries scaled so that the logits are of order one: a code widened to the wrong number moves the scores."""
+    import torch
+    b = _binding()
+    g = np.random.default_rng(500 + band)
+    w = wl.scaled(wl.tiny(), n_layers=1, seqlens=[333], budgets=[80], prior_weight=0.0)
+    d, n = w.head_dim, 333
+    mags = np.arange(16 * band, min(16 * band + 16, 0x7F), dtype=np.uint8)              # 0x7f is NaN
+    k = (g.choice(mags, size=(1, w.n_kv_heads, n, d)) | (g.integers(0, 2, size=(1, w.n_kv_heads, n, d)) << 7)).astype(np.uint8)
+    rms = float(np.sqrt(np.mean(orc.fp8_e4m3_to_f64(mags).astype(np.float64) ** 2)))
+    q = wl.f32_to_bf16_bits((g.standard_normal((1, 1, w.n_q_heads, w.window, d)) * (2.0 / rms)).astype(np.float32))
+    prior = np.zeros(n, dtype=np.float32)
+    prob = b.DeviceProblem(w, q, k, k[:, ::-1].copy(), prior)
+    prob.compress()
+    torch.cuda.synchronize()
+    ref = orc.score_packed(q, k, prior, w.cu_seqlens(), pool_kernel=w.pool_kernel, prior_weight=0.0, k_format="fp8_e4m3")
+    assert ref.std() > 0.2 * ref.mean()                        # the softmax is far from flat: the key values matter
+    pu.assert_scores_close(prob.scores.cpu().numpy(), ref)
+    idx = prob.idx.cpu().numpy()
+    assert np.array_equal(b.DeviceProblem.bits(prob.k_out), pu.host_gather(k, idx, w.cu_seqlens(), w.cu_budgets()))
+    assert np.array_equal(b.DeviceProblem.bits(prob.v_out), pu.host_gather(k[:, ::-1], idx, w.cu_seqlens(), w.cu_budgets()))
+
+
+def test_fp8_scores_equal_the_scores_of_the_same_numbers_in_bf16():
+    """Every E4M3 number is a bf16 number: the two caches holding the same values must give the same bits."""
+    import torch
+    b = _binding()
+    w = wl.scaled(wl.qwen7b_32k(), n_layers=1, seqlens=[2100, 300], budgets=[300, 100])
+    q, k, v, prior = wl.make_all(w)
+    k8 = wl.bf16_bits_to_fp8_codes(k)
+    same = torch.from_numpy(k8).view(torch.float8_e4m3fn).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    p8 = b.DeviceProblem(w, q, k8, k8, prior)
+    p16 = b.DeviceProblem(w, q, same, same, prior)
+    p8.compress(); p16.compress()
+    torch.cuda.synchronize()
+    assert torch.equal(p8.scores, p16.scores) and torch.equal(p8.idx, p16.idx)
