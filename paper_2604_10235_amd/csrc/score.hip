@@ -193,6 +193,8 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   // the unit.  (Measured: 4% off pass 2, nothing off pass 1, whose loop is the shorter one.)
 #ifdef CODECOMP_EXP_NO_DEEP
   constexpr bool DEEP = false;
+#elif defined(CODECOMP_EXP_DEEP_BOTH)
+  constexpr bool DEEP = NW > 4;
 #else
   constexpr bool DEEP = NW > 4 && PASS == 2;
 #endif
@@ -804,11 +806,15 @@ static int launch_passes(const Plan& pl, ScoreArgs a, hipStream_t stream, unsign
 template <int D, bool K8>
 static int dispatch_waves(const Plan& pl, const ScoreArgs& a, hipStream_t s, unsigned st) {
   switch (pl.waves) {
+#ifndef CODECOMP_EXP_ONLY_8_WAVES     // experiments: a quick build with the kernels of the bench workload only
     case 1: return launch_passes<D, 1, K8>(pl, a, s, st);
     case 2: return launch_passes<D, 2, K8>(pl, a, s, st);
     case 3: return launch_passes<D, 3, K8>(pl, a, s, st);
     case 4: return launch_passes<D, 4, K8>(pl, a, s, st);
     case 8: return launch_passes<D, 8, K8>(pl, a, s, st);
+#else
+    case 8: if constexpr (D == 128) return launch_passes<D, 8, K8>(pl, a, s, st);
+#endif
   }
   return CODECOMP_EINVAL_SHAPE;
 }
