@@ -10,7 +10,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcodecomp.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "gather.hip", "structure.hip"]
+# the heavy translation units (the MFMA passes, one per head_dim and key type) first: they run side by side
+SOURCES = ["score_pass_d128_bf16.hip", "score_pass_d128_fp8.hip", "score_pass_d64_bf16.hip", "score_pass_d64_fp8.hip",
+           "api.hip", "score.hip", "select.hip", "gather.hip", "structure.hip"]
 # packed fp32 VALU ops are switched off on purpose (device pass only; the host pass ignores it)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"),
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
@@ -27,7 +29,7 @@ def _compile(src: str) -> str:
 
 
 def build_library(verbose: bool = True) -> str:
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 4)) as ex:
         objs = list(ex.map(_compile, SOURCES))
     r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB],
                        capture_output=True, text=True)

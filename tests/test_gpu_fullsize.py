@@ -12,11 +12,13 @@ from tests import parity_util as pu
 pytestmark = pytest.mark.gpu
 
 
-def run_full(w, samples):
+def run_full(w, samples, kv="bf16"):
     """samples: list of (layer, kv_head, request) whose scores are compared with the oracle."""
     import torch
     from paper_2604_10235_amd import binding as b
     q, k, v, prior = wl.make_all(w, threads=16)
+    if kv == "fp8_e4m3":
+        k, v = wl.bf16_bits_to_fp8_codes(k), wl.bf16_bits_to_fp8_codes(v)
     prob = b.DeviceProblem(w, q, k, v, prior)
     prob.compress(); torch.cuda.synchronize()
     sc = prob.scores.cpu().numpy()
@@ -39,7 +41,7 @@ def run_full(w, samples):
     worst = 0.0
     for (l, h, r) in samples:
         a, e = int(cu[r]), int(cu[r + 1])
-        ref = orc.score(orc.bf16_bits_to_f64(q[l, r, h * G:(h + 1) * G]), orc.bf16_bits_to_f64(k[l, h:h + 1, a:e]),
+        ref = orc.score(orc.bf16_bits_to_f64(q[l, r, h * G:(h + 1) * G]), orc.keys_to_f64(k[l, h:h + 1, a:e], kv),
                         prior[a:e], pool_kernel=w.pool_kernel, prior_weight=w.prior_weight)
         worst = max(worst, pu.assert_scores_close(sc[l, h, a:e], ref[0], what=f"scores[{l},{h},{r}]"))
         idx_ref = orc.select(ref, W, w.budgets[r])[0]
@@ -68,3 +70,7 @@ def test_long_128k_one_layer():
     # W = 128, G = 7: 896 rows in two row splits, 64 chunks per head, budget partly forced by the prior
     w = wl.scaled(wl.long_128k(), n_layers=1)
     run_full(w, [(0, 1, 0)])
+
+
+def test_qwen7b_32k_all_layers_fp8_cache():
+    run_full(wl.qwen7b_32k(), [(0, 1, 0), (14, 0, 0), (27, 3, 0)], kv="fp8_e4m3")
