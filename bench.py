@@ -143,7 +143,7 @@ def main() -> int:
     dom = max(("score_row_stats", "score_mass"), key=lambda n: stage_ms[n])
     flops = 2.0 * w.group * w.window * T * w.head_dim * w.n_kv_heads * L
     achieved = flops / (stage_ms[dom] * 1e-3) / 1e12
-    traffic = read_traffic(w.name)
+    traffic = read_traffic(w.name if args.kv_dtype == "bf16" else f"{w.name}_{args.kv_dtype}")
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": None if not traffic else traffic.get(f"{dom}_hbm_bytes_per_launch"),
