@@ -74,3 +74,10 @@ def test_long_128k_one_layer():
 
 def test_qwen7b_32k_all_layers_fp8_cache():
     run_full(wl.qwen7b_32k(), [(0, 1, 0), (14, 0, 0), (27, 3, 0)], kv="fp8_e4m3")
+
+
+def test_one_million_tokens_in_one_request():
+    # far beyond the configurations: 2**20 keys under one head (16384 tiles of one problem spread over the whole
+    # chip, the streaming form of the selection, 50000 kept rows)
+    w = wl.scaled(wl.qwen7b_32k(), n_layers=1, n_q_heads=2, n_kv_heads=1, window=32, seqlens=[1 << 20], budgets=[50000])
+    run_full(w, [(0, 0, 0)])
