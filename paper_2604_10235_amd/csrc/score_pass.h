@@ -21,6 +21,13 @@
 // (row block, half tile) units.  v_mfma_f32_32x32x16_bf16: the A and B fragments have the same lane layout
 // (lane%32 = row/column, lane/32 = which 8 of the 16 k values), so swapping the operands
 // transposes the output tile without touching the loads.
+//
+// Build switches for measurements, never set in the shipped library: CODECOMP_TRACE (every workgroup records
+// start, end, shader cycles, hardware id and four time marks of its last segment; CODECOMP_TRACE_OUT=<file>
+// makes the host write them after the passes), CODECOMP_EXP_NO_MFMA / _NO_SOFT / _NO_GLOAD / _NO_SSTORE /
+// _NEAR_GLOAD (leave out one ingredient of the tile loop, or keep re-reading the first tile, to see what it
+// costs: the results are wrong on purpose), CODECOMP_PASS1_SAFE_ONLY (pass 1 always with the running
+// maximum), CODECOMP_EXP_ONLY_8_WAVES (instantiate the eight-wave kernels for head_dim 128 only: a quick build).
 #pragma once
 #include <cstdio>
 #include <cstdlib>
@@ -67,7 +74,7 @@ struct ScoreArgs {
 
 #define NEG_BIG (-1.0e30f)
 
-#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+#ifdef CODECOMP_TRACE
 static __device__ long long g_trace[2][2048][4];
 static __device__ long long g_marks[2][2048][4];    // realtime at: chunk located, first tile in LDS, tile loop done, softmax tail done
 static __device__ unsigned char g_simd[2048][8];     // SIMD id of each wave of a workgroup (pass 2)
@@ -149,13 +156,9 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   const int wave = tid >> 6;
   const int l32 = lane & 31;
   const int hf = lane >> 5;
-#ifdef CODECOMP_EXP_CLOCK
+#ifdef CODECOMP_TRACE
   const long long clk0_ = __builtin_readcyclecounter(), rt0_ = __builtin_amdgcn_s_memrealtime();
-#endif
-#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
   long long mark_[4] = {0, 0, 0, 0};
-
-  int nseg_ = 0;
 #endif
   // ---- what this wave owns (the same for every lane: keep it in scalar registers)
   const uint32_t desc = __builtin_amdgcn_readfirstlane(a.wave_desc[wave]);
@@ -184,9 +187,8 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   const int kend = min(n, kstart + ntiles * kTileKeys);
   const int rem = (kend - kstart) & (kTileKeys - 1);        // keys of a partial last tile (0 = it is full)
   const int split_row0 = split * a.nb * 32;
-#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+#ifdef CODECOMP_TRACE
   mark_[0] = __builtin_amdgcn_s_memrealtime();
-  ++nseg_;
 #endif
 
   // ---- K tile staging: global -> registers -> LDS.  Rows past the end of the chunk re-read its
@@ -195,13 +197,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   // Workgroups that have a compute unit to themselves (more than four waves) keep two tiles in flight in two
   // register sets in pass 2: with nothing else resident, a tile that arrives late stalls every SIMD of
   // the unit.  (Measured: 4% off pass 2, nothing off pass 1, whose loop is the shorter one.)
-#ifdef CODECOMP_EXP_NO_DEEP
-  constexpr bool DEEP = false;
-#elif defined(CODECOMP_EXP_DEEP_BOTH)
-  constexpr bool DEEP = NW > 4;
-#else
   constexpr bool DEEP = NW > 4 && PASS == 2;
-#endif
   stage_t stage[LD];
   stage_t stage2[DEEP ? LD : 1];
   // byte offset of this thread's first piece inside a tile; its i-th piece is NT / CH_PER_ROW rows further
@@ -527,7 +523,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     CODECOMP_GLOAD(kstart + kTileKeys, stage)
     if constexpr (DEEP) CODECOMP_GLOAD(kstart + 2 * kTileKeys, stage2)
     lds_barrier();
-#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+#ifdef CODECOMP_TRACE
     mark_[1] = __builtin_amdgcn_s_memrealtime();
 #endif
 #pragma unroll
@@ -560,13 +556,13 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
       reduce_cols(ntiles - 3);
       tile_body(ntiles - 1, std::true_type{}, fast, a1, b1, stg_none{});
     }
-#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+#ifdef CODECOMP_TRACE
     mark_[2] = __builtin_amdgcn_s_memrealtime();
 #endif
 #pragma unroll
     for (int m = 0; m < MS; ++m) soft_step(accB0, accB1, m, b1, fast);
     soft_end(ntiles - 1, 1, b1, fast);
-#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+#ifdef CODECOMP_TRACE
     mark_[3] = __builtin_amdgcn_s_memrealtime();
 #endif
   };
@@ -618,8 +614,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   lds_barrier();
   x += ntiles;
   }   // segments
-#ifdef CODECOMP_EXP_CLOCK
-#if CODECOMP_EXP_CLOCK == 2     // one record per workgroup: where and when it ran
+#ifdef CODECOMP_TRACE     // one record per workgroup: where and when it ran
   if (lane == 0 && PASS == 2) {
     const int idx_ = blockIdx.x;
     if (idx_ < 2048 && wave < 8) g_simd[idx_][wave] = (unsigned char)((__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 4) & 3);
@@ -636,12 +631,6 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
                                    ((long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32);
     }
   }
-#else
-  if (tid == 0 && blockIdx.x == gridDim.x / 2)
-    printf("pass %d: %lld shader cycles in %lld ticks of 100 MHz -> %.3f GHz, %d tiles\n", PASS,
-           (long long)(__builtin_readcyclecounter() - clk0_), (long long)(__builtin_amdgcn_s_memrealtime() - rt0_),
-           (double)(__builtin_readcyclecounter() - clk0_) / (double)(__builtin_amdgcn_s_memrealtime() - rt0_) * 0.1, x_end - x_begin);
-#endif
 #endif
 #undef CODECOMP_GLOAD
 #undef CODECOMP_KEY0
@@ -651,7 +640,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
 // Enqueues the row merge between the two passes (defined in score.hip).
 int launch_row_merge(const Plan& pl, const ScoreArgs& a, hipStream_t stream);
 
-#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+#ifdef CODECOMP_TRACE
 // experiments: after the passes, write what the workgroups recorded (this translation unit's copy of the buffers)
 static void trace_dump() {
   if (const char* path_ = getenv("CODECOMP_TRACE_OUT")) {
@@ -752,7 +741,7 @@ int dispatch_waves_switch(const Plan& pl, const ScoreArgs& a, hipStream_t s, uns
 template <int D, bool K8>
 int dispatch_waves(const Plan& pl, const ScoreArgs& a, hipStream_t s, unsigned st) {
   const int rc = dispatch_waves_switch<D, K8>(pl, a, s, st);
-#if defined(CODECOMP_EXP_CLOCK) && CODECOMP_EXP_CLOCK == 2
+#ifdef CODECOMP_TRACE
   if (rc == 0) trace_dump();
 #endif
   return rc;
