@@ -42,7 +42,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // 16-byte register quantum for loads/stores and MFMA fragments (a native vector: plain loads, no struct copies)
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 struct ScoreArgs {
   const uint16_t* q;
@@ -83,16 +82,15 @@ static __device__ unsigned char g_simd[2048][8];     // SIMD id of each wave of 
 __device__ __forceinline__ bf16x8 frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // What goes into the LDS tile for one staged piece of 8 key elements: bf16 as it is; 8 FP8 E4M3 codes widened to
-// bf16.  Every E4M3 number is a bf16 number, so the conversion to f32 followed by dropping the low 16 bits is exact.
+// bf16 (exact: every E4M3 number is a bf16 number).  v_cvt_scalef32_pk_bf16_fp8 turns the two codes in the low
+// or the high half of its source into two bf16, times a power of two taken from the float operand (2^0 here).
 __device__ __forceinline__ u32x4 to_bf16x8(u32x4 v) { return v; }
 __device__ __forceinline__ u32x4 to_bf16x8(u32x2 v) {
-  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)v.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)v.x, true);
-  const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)v.y, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)v.y, true);
-  u32x4 r;      // v_perm: bytes 2,3 of the second operand, then bytes 2,3 of the first
-  r.x = __builtin_amdgcn_perm(__float_as_uint(a.y), __float_as_uint(a.x), 0x07060302u);
-  r.y = __builtin_amdgcn_perm(__float_as_uint(b.y), __float_as_uint(b.x), 0x07060302u);
-  r.z = __builtin_amdgcn_perm(__float_as_uint(c.y), __float_as_uint(c.x), 0x07060302u);
-  r.w = __builtin_amdgcn_perm(__float_as_uint(d.y), __float_as_uint(d.x), 0x07060302u);
+  u32x4 r;
+  r.x = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.x, 1.0f, false));
+  r.y = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.x, 1.0f, true));
+  r.z = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.y, 1.0f, false));
+  r.w = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.y, 1.0f, true));
   return r;
 }
 
