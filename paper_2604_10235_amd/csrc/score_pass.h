@@ -192,10 +192,11 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   // ---- K tile staging: global -> registers -> LDS.  Rows past the end of the chunk re-read its
   // last key (always in bounds); such columns are masked (pass 1) or never stored (pass 2).
   const unsigned char* kb = a.k + ((int64_t)layer * a.kv_sl + (int64_t)head * a.kv_sh + (int64_t)tok0 * a.kv_st) * ESZ;
-  // Workgroups that have a compute unit to themselves (more than four waves) keep two tiles in flight in two
-  // register sets in pass 2: with nothing else resident, a tile that arrives late stalls every SIMD of
-  // the unit.  (Measured: 4% off pass 2, nothing off pass 1, whose loop is the shorter one.)
-  constexpr bool DEEP = NW > 4 && PASS == 2;
+  // Workgroups of four or eight waves keep two tiles in flight in two register sets in pass 2: a tile that
+  // arrives late stalls every SIMD the workgroup runs on.  (Measured: 4% off pass 2 with eight waves, one
+  // workgroup per compute unit; 6% with four waves, two per unit; nothing off pass 1, whose loop is the
+  // shorter one.)
+  constexpr bool DEEP = NW >= 4 && PASS == 2;
   stage_t stage[LD];
   stage_t stage2[DEEP ? LD : 1];
   // byte offset of this thread's first piece inside a tile; its i-th piece is NT / CH_PER_ROW rows further
