@@ -94,18 +94,47 @@ __device__ __forceinline__ u32x4 to_bf16x8(u32x2 v) {
   return r;
 }
 
-// Request that holds position `xr` of a (layer*head, row split) sequence; tile_in_seq < 0 inside the lead.
-__device__ __forceinline__ void locate_tile(const int32_t* cu, int n_seqs, int lead, int trim, int xr, int& seq, int& tok0,
-                                            int& n, int& tile_in_seq, int& tiles_of_seq) {
-  int acc = 0;
-  for (int r = 0; r < n_seqs; ++r) {
-    const int a = cu[r], b = cu[r + 1];
-    const int nt = (b - a - trim + kTileKeys - 1) / kTileKeys;      // keys of the request: all but the last `trim`
-    if (xr < acc + lead + nt || r == n_seqs - 1) {
-      seq = r; tok0 = a; n = b - a - trim; tile_in_seq = xr - acc - lead; tiles_of_seq = nt;
-      return;
+// Positions that request r takes in the tile sequence of a problem: its lead and its tiles.
+__device__ __forceinline__ int tiles_of(int len, int trim) { return (len - trim + kTileKeys - 1) / kTileKeys; }
+
+// Where a workgroup enters a problem's sequence: the request that holds position `xr` and the position at which
+// that request's lead begins.  All threads of the workgroup call it together (two barriers): every thread adds up
+// a contiguous share of the requests, a prefix sum over the threads finds the share that holds xr, and its owner
+// walks that share.  The segment loop then only ever steps from one request to the next.
+template <int NT>
+__device__ __forceinline__ void locate_first(const int32_t* cu, int n_seqs, int lead, int trim, int xr, int& seq, int& acc) {
+  __shared__ int wave_total[NT / 64];
+  __shared__ int found[2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = (n_seqs + NT - 1) / NT;
+  const int r0 = min(tid * per, n_seqs), r1 = min(r0 + per, n_seqs);
+  int mine = 0;
+  for (int r = r0; r < r1; ++r) mine += lead + tiles_of(cu[r + 1] - cu[r], trim);
+  int incl = mine;                                   // inclusive prefix sum inside the wave
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int up = __shfl_up(incl, off);
+    if (lane >= off) incl += up;
+  }
+  if (lane == 63) wave_total[wave] = incl;
+  if (tid == 0) { found[0] = n_seqs - 1; found[1] = -1; }
+  __syncthreads();
+  int start = incl - mine;
+  for (int w = 0; w < wave; ++w) start += wave_total[w];
+  if (xr >= start && xr < start + mine) {            // exactly one thread, when xr lies inside the sequence
+    int pos = start, r = r0;
+    for (;; ++r) {
+      const int span = lead + tiles_of(cu[r + 1] - cu[r], trim);
+      if (xr < pos + span) break;
+      pos += span;
     }
-    acc += lead + nt;
+    found[0] = r; found[1] = pos;
+  }
+  __syncthreads();
+  seq = found[0]; acc = found[1];
+  if (acc < 0) {                                     // past the end (never for a position inside the sequence): last request
+    acc = 0;
+    for (int r = 0; r < n_seqs - 1; ++r) acc += lead + tiles_of(cu[r + 1] - cu[r], trim);
   }
 }
 
@@ -166,14 +195,30 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   // ---- this workgroup's share of the tile sequence, one segment (part of one problem) at a time
   const int x_begin = (int)((int64_t)blockIdx.x * a.total_tiles / gridDim.x);
   const int x_end = (int)((int64_t)(blockIdx.x + 1) * a.total_tiles / gridDim.x);
+  // the request the walk stands in: request cur_seq of problem cur_hi, whose lead begins at position cur_acc
+  int cur_hi = x_begin / a.tiles_per_problem, cur_seq = 0, cur_acc = 0;
+  if (a.n_seqs > 16 && x_begin < x_end)                      // few requests: walking there from the first one is as quick
+    locate_first<NT>(a.cu_seqlens, a.n_seqs, a.lead, a.key_trim, x_begin - cur_hi * a.tiles_per_problem, cur_seq, cur_acc);
+  cur_seq = __builtin_amdgcn_readfirstlane(cur_seq);         // the same in every lane: scalar registers from here on
+  cur_acc = __builtin_amdgcn_readfirstlane(cur_acc);
   for (int x = x_begin; x < x_end;) {
   const int hi = x / a.tiles_per_problem;                  // (layer * Hkv + head) * row_splits + split
   const int lz = hi / a.row_splits;
   const int split = hi - lz * a.row_splits;
   const int layer = lz / a.Hkv;
   const int head = lz - layer * a.Hkv;
-  int seq, tok0, n, tile_in_seq, tiles_of_seq;
-  locate_tile(a.cu_seqlens, a.n_seqs, a.lead, a.key_trim, x - hi * a.tiles_per_problem, seq, tok0, n, tile_in_seq, tiles_of_seq);
+  if (hi != cur_hi) { cur_hi = hi; cur_seq = 0; cur_acc = 0; }     // crossed into the next problem: its first request
+  const int xr = x - hi * a.tiles_per_problem;
+  int tok0 = a.cu_seqlens[cur_seq], tok1 = a.cu_seqlens[cur_seq + 1];
+  int tiles_of_seq = tiles_of(tok1 - tok0, a.key_trim);
+  while (xr >= cur_acc + a.lead + tiles_of_seq && cur_seq < a.n_seqs - 1) {       // usually no step or one
+    cur_acc += a.lead + tiles_of_seq;
+    ++cur_seq;
+    tok0 = tok1; tok1 = a.cu_seqlens[cur_seq + 1];
+    tiles_of_seq = tiles_of(tok1 - tok0, a.key_trim);
+  }
+  const int seq = cur_seq, n = tok1 - tok0 - a.key_trim;     // keys of the request: all but the last key_trim
+  int tile_in_seq = xr - cur_acc - a.lead;                   // < 0 inside the lead
   if (tile_in_seq < 0) {                                    // inside the lead: the problem's tiles start after it
     x -= tile_in_seq;
     tile_in_seq = 0;

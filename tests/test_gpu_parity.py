@@ -330,6 +330,22 @@ def test_logits_that_outrun_the_first_tile_reference():
     assert np.all(np.abs(mass - w.window) < 0.02 * w.window)
 
 
+@pytest.mark.parametrize("wgs", [0, 5, 61, 2048])
+@pytest.mark.parametrize("variant", [0, 8])
+def test_workgroups_enter_the_tile_sequence_anywhere(wgs, variant, monkeypatch):
+    """More than 16 requests: a workgroup finds the request its range starts in with a cooperative search and then
+    walks from request to request.  Forced grid sizes put the range starts anywhere (inside leads, on the last
+    request, in the second problem); with the prefix-only softmax some requests have no tile at all."""
+    if wgs:
+        monkeypatch.setenv("CODECOMP_SCORE_WGS", str(wgs))
+    rng = np.random.default_rng(77)
+    lens = [int(x) for x in rng.choice([32, 33, 64, 100, 257, 900, 2100], size=45)]
+    lens[7] = 32; lens[44] = 32                                       # nothing but the window (also as the last request)
+    w = wl.scaled(wl.ragged_agentic(), n_layers=2, seqlens=lens, budgets=[max(32, n // 4) for n in lens], window=32,
+                  n_kv_heads=2, n_q_heads=6)
+    run_case(w, variant=variant)
+
+
 def test_many_short_requests():
     """300 packed requests of 40..167 tokens: every per-request lookup (tile sequence, merge, pooling, select) at scale."""
     rng = np.random.default_rng(5)
