@@ -57,6 +57,10 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2604_10235_amd.build)")
+        # The device memory and the streams that this binding hands to the library come from torch, which ships
+        # its own HIP runtime.  Loaded first, that runtime is the one the library binds to; the other way round
+        # the process ends up with two runtimes and every launch fails with hipErrorNoDevice.
+        import torch  # noqa: F401
         l = C.CDLL(LIB_PATH)
         P = C.POINTER(codecomp_params)
         l.codecomp_workspace_bytes.restype = C.c_size_t
