@@ -55,18 +55,30 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
   const unsigned char* vb = a.v + layer * a.kv_sl + head * a.kv_sh;
   unsigned char* ko = a.k_out + layer * a.o_sl + head * a.o_sh;
   unsigned char* vo = a.v_out + layer * a.o_sl + head * a.o_sh;
-  const int slot0 = blockIdx.x * rows_per_pass * kGatherRowsPerThread + rsub;
+  const int first_slot = blockIdx.x * rows_per_pass * kGatherRowsPerThread;
+  const int slot0 = first_slot + rsub;
+
+  // Request that owns the workgroup's first output slot: a 256-way search by the whole workgroup (thread t
+  // probes the t-th of 256 evenly spaced candidates; the probes that are not beyond the slot form a prefix),
+  // one round per factor of 256 in n_seqs instead of one dependent load per factor of 2.  The rows of the
+  // workgroup then walk forward from there (they lie within a few dozen slots of the first).
+  int r_first = 0;
+  for (int span = a.n_seqs; span > 1;) {
+    const int step = (span + kGatherThreads - 1) / kGatherThreads;
+    const int r = r_first + (int)threadIdx.x * step;
+    const int hits = __syncthreads_count(r < r_first + span && a.cu_budgets[r] <= first_slot);   // >= 1: cu_budgets[r_first] <= first_slot
+    const int next = r_first + (hits - 1) * step;
+    span = min(step, r_first + span - next);
+    r_first = next;
+  }
 
   u32x4 kv[kGatherRowsPerThread], vv[kGatherRowsPerThread];
 #pragma unroll
   for (int i = 0; i < kGatherRowsPerThread; ++i) {
     const int slot = slot0 + i * rows_per_pass;
     if (slot < a.TB) {
-      int lo = 0, hi = a.n_seqs;          // request owning this output slot
-      while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (a.cu_budgets[mid] <= slot) lo = mid; else hi = mid;
-      }
+      int lo = r_first;                   // request owning this output slot
+      while (lo + 1 < a.n_seqs && a.cu_budgets[lo + 1] <= slot) ++lo;
       // indices are clamped into the request so that a corrupt idx can never read out of bounds
       const int s0 = a.cu_seqlens[lo], n = a.cu_seqlens[lo + 1] - s0;
       const int64_t tok = (int64_t)s0 + min(max(idx[slot], 0), n - 1);
