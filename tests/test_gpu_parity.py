@@ -449,3 +449,26 @@ def test_fp8_scores_equal_the_scores_of_the_same_numbers_in_bf16():
     p8.compress(); p16.compress()
     torch.cuda.synchronize()
     assert torch.equal(p8.scores, p16.scores) and torch.equal(p8.idx, p16.idx)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_valid_shapes(seed):
+    """Seeded random draws over everything the parameters allow at small sizes: head counts and group sizes (one to
+    sixteen row blocks: every wave count and row-block layout), window, head_dim, request mix, pool width, prior
+    weight, score-tail variants, cache type; additive selection against the oracle as in every other case."""
+    g = np.random.default_rng(9000 + seed)
+    d = int(g.choice([64, 128]))
+    h_kv = int(g.integers(1, 4))
+    group = int(g.integers(1, 9))
+    window = int(g.choice([1, 7, 16, 32, 33, 48, 64, 96]))
+    n_seqs = int(g.integers(1, 5))
+    lens = [int(window + g.integers(0, 1800)) for _ in range(n_seqs)]
+    budgets = [int(g.integers(window, n + 1)) for n in lens]
+    variant = int(g.choice([0, 0, 1, 4, 8, 16, 8 | 16, 1 | 4]))
+    if window % 32 == 0 and group * window <= 512 and g.random() < 0.3:
+        variant = (variant & ~1) | 2                                   # largest head mass
+    kv = "fp8_e4m3" if g.random() < 0.35 else "bf16"
+    w = wl.scaled(wl.qwen7b_32k(), name=f"rand{seed}", n_layers=int(g.integers(1, 3)), seqlens=lens, budgets=budgets,
+                  window=window, head_dim=d, n_kv_heads=h_kv, n_q_heads=h_kv * group,
+                  pool_kernel=int(g.choice([1, 3, 5, 7, 9, 21])), prior_weight=float(g.choice([0.0, 0.5, 1.0, 3.0])))
+    run_case(w, fused=bool(g.integers(0, 2)), variant=variant, kv=kv)
