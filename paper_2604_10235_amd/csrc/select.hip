@@ -436,16 +436,17 @@ __global__ __launch_bounds__(kSelectThreads) void select_stage2_kernel(SelectArg
 // candidates kept in registers per thread, chosen from the longest request
 static int items_for(const Plan& pl) {
   const int npre = pl.max_n - pl.W;
-  if (npre <= kSelectThreads * 8) return 8;
-  if (npre <= kSelectThreads * 32) return 32;
-  if (npre <= kSelectThreads * 64) return 64;
+  for (int items : {8, 16, 32, 48, 64})
+    if (npre <= kSelectThreads * items) return items;
   return 0;
 }
 
 #define CODECOMP_DISPATCH_ITEMS(KERNEL, GRID, ARGS)                                        \
   switch (items_for(pl)) {                                                                 \
     case 8: KERNEL<8><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;             \
+    case 16: KERNEL<16><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
     case 32: KERNEL<32><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
+    case 48: KERNEL<48><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
     case 64: KERNEL<64><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
     default: KERNEL<0><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;            \
   }

@@ -156,6 +156,8 @@ def test_prefix_softmax_without_any_prefix():
     dict(seqlens=[777], budgets=[99], window=32, pool_kernel=31),      # wide pooling
     dict(seqlens=[1500], budgets=[200], window=32, head_dim=64, n_q_heads=8),   # d = 64 with a group of 2
     dict(seqlens=[3000], budgets=[400], window=32, pool_kernel=1025),  # the widest pooling the path takes
+    dict(seqlens=[12000], budgets=[900], window=32),                   # selection with 16 candidates per thread in registers
+    dict(seqlens=[40000, 9000], budgets=[3000, 700], window=32),       # ... and with 48 (chosen from the longest request)
     dict(seqlens=[1500], budgets=[200], window=64, head_dim=64, n_q_heads=28),  # d = 64 with eight waves (448 rows)
     dict(seqlens=[2000, 600], budgets=[700, 512], window=512, n_q_heads=8, n_kv_heads=2),   # 2048 rows: four row splits
     dict(seqlens=[1100], budgets=[1050], window=1024, n_q_heads=64, n_kv_heads=1),  # 65536 rows: the most the path takes
