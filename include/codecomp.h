@@ -12,9 +12,11 @@
  *
  * Conventions shared by every entry point
  *   - All data pointers are DEVICE pointers unless the name ends in _host.  bf16 tensors are
- *     passed as `const void*` (16-bit patterns).  The library allocates nothing, keeps no
- *     state and never synchronises: work is enqueued on `hip_stream` (a hipStream_t passed as
- *     void*; NULL = the default stream) and the call returns.
+ *     passed as `const void*` (16-bit patterns).  The library allocates nothing and never
+ *     synchronises: work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and the call returns.  It reads no environment variable, and all it remembers
+ *     between calls is, per device, how many workgroups of each score kernel fit on the device at
+ *     once (asked of the runtime on the first call that needs it): calls are re-entrant.
  *   - Query head h_q reads KV head h_q / G with G = n_q_heads / n_kv_heads; the G heads of a
  *     group are averaged.
  *   - Requests are packed along the token axis: request r owns tokens
@@ -49,7 +51,8 @@ extern "C" {
 enum {
   CODECOMP_OK = 0,
   CODECOMP_EINVAL_NULL = -1,      /* a required pointer is NULL                                  */
-  CODECOMP_EINVAL_SHAPE = -2,     /* n_layers < 1, n_seqs < 1, a negative stride, G*W too large   */
+  CODECOMP_EINVAL_SHAPE = -2,     /* n_layers < 1, n_seqs < 1, a negative stride, G*W too large,
+                                     score_workgroups < 0, score_lead_tiles > 64                    */
   CODECOMP_EINVAL_WINDOW = -3,    /* W < 1 or W > N_r for some request                            */
   CODECOMP_EINVAL_BUDGET = -4,    /* B_r < W or B_r > N_r for some request                        */
   CODECOMP_EINVAL_POOL = -5,      /* pool_kernel even, < 1 or > 1025                              */
@@ -86,6 +89,12 @@ typedef struct codecomp_params {
   int32_t span_budget_min;     /* B_min >= 0                                                      */
   int32_t score_variant;       /* bit flags CODECOMP_VARIANT_*; 0 = the default readings          */
   int32_t kv_dtype;            /* CODECOMP_KV_BF16 (0) or CODECOMP_KV_FP8_E4M3 (1): element type of k, v, k_out, v_out */
+  /* How the two logit passes of codecomp_score are cut into workgroups; the results do not depend on either
+   * value beyond the regrouping of fp32 sums (for tests of exactly that, and for tuning).  Leave both 0. */
+  int32_t score_workgroups;    /* 0 = as many as the device holds at once; n > 0 = n (at most 2048, at most one per
+                                  64-key tile)                                                       */
+  int32_t score_lead_tiles;    /* weight, in 64-key tiles, given to the start of a request when the tiles are shared
+                                  out: 0 = built-in value, < 0 = none, 1..64 = that many             */
 } codecomp_params;
 
 /* Other readings of what the paper leaves open about the tail of the score step (section
@@ -181,12 +190,21 @@ int codecomp_select_two_stage(const float* scores, const float* prior, const cod
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* k_out[l][h][cu_budgets[r] + i][:] = k[l][h][cu_seqlens[r] + idx[l][h][cu_budgets[r] + i]][:],
- * same for v: a bit copy of the retained rows (the compact per-layer cache).  idx values must lie
- * in [0, N_r). */
+ * same for v: a bit copy of the retained rows.  This builds the compressed chunk of section "Position
+ * Encoding" (the retained tokens of a chunk, in their original order, which is what lets them keep their
+ * original position indices), once per layer because section "Attention-based KV Cache Compression" applies the
+ * compression independently at each transformer layer.  idx values must lie in [0, N_r) (values outside are
+ * clamped into the request, so a corrupt index cannot read out of bounds); rows are moved as 16-byte pieces. */
 int codecomp_gather(const void* k, const void* v, const int32_t* idx, const codecomp_params* params,
                     void* k_out, void* v_out, void* hip_stream);
 
-/* The three steps above enqueued back to back in one call; `scores` and `idx` are outputs too. */
+/* The compression of section "Attention-based KV Cache Compression" from end to end, for every layer, KV head
+ * and request of the batch: window attention mass (the equation of that section) -> pooled, fused with the
+ * prior -> the best-scored context tokens kept up to the budget -> their K/V rows copied into the compact
+ * cache.  Exactly codecomp_score, then codecomp_select (or codecomp_select_two_stage when
+ * params->select_mode says so), then codecomp_gather, enqueued back to back on `hip_stream`; `scores` and
+ * `idx` are outputs too.  Arguments, layouts and errors as for those calls; nothing is enqueued when an
+ * argument is rejected. */
 int codecomp_compress(const void* q_obs, const void* k, const void* v, const float* prior,
                       const codecomp_params* params, float* scores, int32_t* idx, void* k_out, void* v_out,
                       void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -38,6 +38,7 @@ class codecomp_params(C.Structure):
         ("out_stride_layer", C.c_int64), ("out_stride_head", C.c_int64), ("out_stride_tok", C.c_int64),
         ("span_budget_ratio", C.c_float), ("span_budget_min", C.c_int32),
         ("score_variant", C.c_int32), ("kv_dtype", C.c_int32),
+        ("score_workgroups", C.c_int32), ("score_lead_tiles", C.c_int32),
     ]
 
 
@@ -124,7 +125,7 @@ def make_params(*, n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int
     p.cu_budgets_host = cbl.ctypes.data
     p.cu_seqlens_dev = cu_seqlens_dev
     p.cu_budgets_dev = cu_budgets_dev
-    for name, val in strides.items():      # strides, select_mode, span_budget_*
+    for name, val in strides.items():      # strides, select_mode, span_budget_*, score_variant, kv_dtype, score_workgroups ...
         setattr(p, name, val)
     p._keep = (csl, cbl)
     return p
@@ -234,7 +235,7 @@ class DeviceProblem:
 
     def __init__(self, w, q_bits: np.ndarray, k_bits: np.ndarray, v_bits: Optional[np.ndarray], prior: np.ndarray,
                  device: str = "cuda:0", select_mode: int = 0, span_budget_ratio: float = 0.5,
-                 span_budget_min: int = 0, score_variant: int = 0):
+                 span_budget_min: int = 0, score_variant: int = 0, score_workgroups: int = 0, score_lead_tiles: int = 0):
         import torch
         self.w = w
         dev = torch.device(device)
@@ -262,7 +263,8 @@ class DeviceProblem:
                                   cu_budgets_host=w.cu_budgets(), cu_seqlens_dev=_ptr(self.cu_seqlens),
                                   cu_budgets_dev=_ptr(self.cu_budgets), select_mode=select_mode,
                                   span_budget_ratio=span_budget_ratio, span_budget_min=span_budget_min,
-                                  score_variant=score_variant, kv_dtype=KV_FP8_E4M3 if fp8 else KV_BF16)
+                                  score_variant=score_variant, kv_dtype=KV_FP8_E4M3 if fp8 else KV_BF16,
+                                  score_workgroups=score_workgroups, score_lead_tiles=score_lead_tiles)
         rc = codecomp_validate(self.params)
         _check(rc, "codecomp_validate")
         T, TB = w.total_tokens, w.total_budget

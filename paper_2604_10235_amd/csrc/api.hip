@@ -2,7 +2,6 @@
 // score -> select -> gather path.  Everything here runs on the host; validation happens before
 // the first HIP call so that rejected arguments never reach a GPU.
 #include <math.h>
-#include <stdlib.h>
 
 #include "plan.h"
 
@@ -120,11 +119,9 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   assign_row_blocks(pl);
   // the largest head mass is taken per workgroup from whole row blocks: one head per block, all rows in one workgroup
   if ((pl->variant & CODECOMP_VARIANT_GROUP_MAX) && (pl->W % 32 != 0 || pl->row_splits != 1)) return CODECOMP_EINVAL_MODE;
-  pl->lead_tiles = kLeadTiles;
-  if (const char* e = getenv("CODECOMP_SCORE_LEAD_TILES")) {   // tuning experiments
-    const int v = atoi(e);
-    if (v >= 0 && v <= 64) pl->lead_tiles = v;
-  }
+  if (p->score_workgroups < 0 || p->score_lead_tiles > 64) return CODECOMP_EINVAL_SHAPE;
+  pl->grid_override = p->score_workgroups;
+  pl->lead_tiles = p->score_lead_tiles == 0 ? kLeadTiles : (p->score_lead_tiles < 0 ? 0 : p->score_lead_tiles);
   int64_t tiles = 0;
   for (int r = 0; r < p->n_seqs; ++r) {
     int n = p->cu_seqlens_host[r + 1] - p->cu_seqlens_host[r] - pl->key_trim;     // >= 0: W <= N_r was checked

@@ -18,30 +18,12 @@ struct GatherArgs {
   int64_t kv_sl, kv_sh, kv_st, o_sl, o_sh, o_st;     // in bytes
 };
 
-#ifndef CODECOMP_GATHER_ROWS
-#define CODECOMP_GATHER_ROWS 2
-#endif
-#ifndef CODECOMP_GATHER_NT
-#define CODECOMP_GATHER_NT 0
-#endif
 constexpr int kGatherThreads = 256;
-constexpr int kGatherRowsPerThread = CODECOMP_GATHER_ROWS;
+constexpr int kGatherRowsPerThread = 2;     // rows of K and of V a thread has in flight
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ u32x4 ld16(const unsigned char* p) {
-#if CODECOMP_GATHER_NT
-  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-#else
-  return *reinterpret_cast<const u32x4*>(p);
-#endif
-}
-__device__ __forceinline__ void st16(unsigned char* p, u32x4 v) {
-#if CODECOMP_GATHER_NT
-  __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
-#else
-  *reinterpret_cast<u32x4*>(p) = v;
-#endif
-}
+__device__ __forceinline__ u32x4 ld16(const unsigned char* p) { return *reinterpret_cast<const u32x4*>(p); }
+__device__ __forceinline__ void st16(unsigned char* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
 
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
   const int pieces = 1 << a.pieces_log2;

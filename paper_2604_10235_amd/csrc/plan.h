@@ -35,6 +35,7 @@ struct Plan {
   // ones slot 1 covers (0: the wave has no slot 1).
   uint32_t wave_desc[kMaxWaves];
   uint8_t rb_holder[2 * kMaxWaves][2];   // per row block: wave * 2 + slot of its (one or two) owners, 255 = none
+  int grid_override;         // > 0: the caller fixed the number of workgroups of the score passes
   int lead_tiles;            // empty positions before each request's tiles in the sequence below: the cost of starting a segment
   int tiles_per_problem;     // sum over requests of (lead_tiles + ceil(N_r / kTileKeys)): positions of one (layer, head, row split)
   int total_tiles;           // L * Hkv * row_splits * tiles_per_problem, shared out evenly over the workgroups

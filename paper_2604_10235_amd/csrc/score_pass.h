@@ -21,16 +21,8 @@
 // (row block, half tile) units.  v_mfma_f32_32x32x16_bf16: the A and B fragments have the same lane layout
 // (lane%32 = row/column, lane/32 = which 8 of the 16 k values), so swapping the operands
 // transposes the output tile without touching the loads.
-//
-// Build switches for measurements, never set in the shipped library: CODECOMP_TRACE (every workgroup records
-// start, end, shader cycles, hardware id and four time marks of its last segment; CODECOMP_TRACE_OUT=<file>
-// makes the host write them after the passes), CODECOMP_EXP_NO_MFMA / _NO_SOFT / _NO_GLOAD / _NO_SSTORE /
-// _NEAR_GLOAD (leave out one ingredient of the tile loop, or keep re-reading the first tile, to see what it
-// costs: the results are wrong on purpose), CODECOMP_PASS1_SAFE_ONLY (pass 1 always with the running
-// maximum), CODECOMP_EXP_ONLY_8_WAVES (instantiate the eight-wave kernels for head_dim 128 only: a quick build).
 #pragma once
-#include <cstdio>
-#include <cstdlib>
+#include <atomic>
 #include <type_traits>
 
 #include "plan.h"
@@ -73,11 +65,6 @@ struct ScoreArgs {
 
 #define NEG_BIG (-1.0e30f)
 
-#ifdef CODECOMP_TRACE
-static __device__ long long g_trace[2][2048][4];
-static __device__ long long g_marks[2][2048][4];    // realtime at: chunk located, first tile in LDS, tile loop done, softmax tail done
-static __device__ unsigned char g_simd[2048][8];     // SIMD id of each wave of a workgroup (pass 2)
-#endif
 
 __device__ __forceinline__ bf16x8 frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -147,10 +134,6 @@ __device__ __forceinline__ int wg_of_tile(int x, int total, int wgs) {
 // (output lane = query row), PASS 2 the queries (output lane = key).
 template <int PASS>
 __device__ __forceinline__ f32x16 mma_step(u32x4 qfrag, u32x4 kfrag, f32x16 acc) {
-#ifdef CODECOMP_EXP_NO_MFMA
-  acc[0] += __uint_as_float(qfrag.x ^ kfrag.x) * 1e-30f;   // keeps the operand loads alive, one VALU op
-  return acc;
-#endif
   if constexpr (PASS == 1)
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(kfrag), frag(qfrag), acc, 0, 0, 0);
   else
@@ -183,10 +166,6 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   const int wave = tid >> 6;
   const int l32 = lane & 31;
   const int hf = lane >> 5;
-#ifdef CODECOMP_TRACE
-  const long long clk0_ = __builtin_readcyclecounter(), rt0_ = __builtin_amdgcn_s_memrealtime();
-  long long mark_[4] = {0, 0, 0, 0};
-#endif
   // ---- what this wave owns (the same for every lane: keep it in scalar registers)
   const uint32_t desc = __builtin_amdgcn_readfirstlane(a.wave_desc[wave]);
   const int rb_of[2] = {(int)(desc & 255u), (int)((desc >> 8) & 255u)};
@@ -230,9 +209,6 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   const int kend = min(n, kstart + ntiles * kTileKeys);
   const int rem = (kend - kstart) & (kTileKeys - 1);        // keys of a partial last tile (0 = it is full)
   const int split_row0 = split * a.nb * 32;
-#ifdef CODECOMP_TRACE
-  mark_[0] = __builtin_amdgcn_s_memrealtime();
-#endif
 
   // ---- K tile staging: global -> registers -> LDS.  Rows past the end of the chunk re-read its
   // last key (always in bounds); such columns are masked (pass 1) or never stored (pass 2).
@@ -249,14 +225,9 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   const uint32_t soff0 = (uint32_t)((tid / CH_PER_ROW) * (int)a.kv_st + (tid % CH_PER_ROW) * 8) * (uint32_t)ESZ;
   const uint32_t sstep = (uint32_t)((NT / CH_PER_ROW) * (int)a.kv_st) * (uint32_t)ESZ;
   // fast path: every staged row (slack rows included) lies inside the chunk -> uniform base + lane offset
-#ifdef CODECOMP_EXP_NEAR_GLOAD   /* experiment: always re-read the first tile of the segment (cache hits) */
-#define CODECOMP_KEY0(X) (((X) & 0) + kstart)
-#else
-#define CODECOMP_KEY0(X) (X)
-#endif
 #define CODECOMP_GLOAD(KEY0, ST)                                                                    \
   {                                                                                                 \
-    const int key0_ = CODECOMP_KEY0(KEY0);                                                          \
+    const int key0_ = (KEY0);                                                                       \
     if (key0_ + LDS_ROWS <= kend) {                                                                 \
       const unsigned char* tb_ = kb + (int64_t)key0_ * a.kv_st * ESZ;                              \
       _Pragma("unroll") for (int i = 0; i < LD; ++i)                                                \
@@ -404,10 +375,6 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     constexpr int EXPSTEPS = MS - MAXSTEPS;
     constexpr int EBASE = NE / EXPSTEPS, EEXTRA = NE % EXPSTEPS;
     if (m == 0) { s0 = 0.f; s1 = 0.f; }
-#ifdef CODECOMP_EXP_NO_SOFT
-    s0 += p0[m % 16]; if (BOTH) s1 += p1[m % 16];
-    return;
-#endif
     if constexpr (TRACK_MAX) {
       if (m < MAXSTEPS) {
         constexpr int PER = 16 / MAXSTEPS;      // logits of each slot folded into the maxima per gap
@@ -503,15 +470,11 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     // ---------------- phase a: logits of sub-tile a -> accA; softmax of accB (tile t-1, sub-tile b)
     // tile t+1 waits in staging registers: park it in the other LDS buffer (its last readers passed
     // the previous barrier), then send the loads of a later tile on their way into the same registers
-#ifndef CODECOMP_EXP_NO_SSTORE
     if constexpr (STG == 0 || STG == 1) { CODECOMP_SSTORE(buf ^ 1, stage) }
     if constexpr (STG == 2) { CODECOMP_SSTORE(buf ^ 1, stage2) }
-#endif
-#ifndef CODECOMP_EXP_NO_GLOAD
     if constexpr (STG == 0) CODECOMP_GLOAD(kstart + (t + 2) * kTileKeys, stage)
     if constexpr (STG == 1) CODECOMP_GLOAD(kstart + (t + 3) * kTileKeys, stage)
     if constexpr (STG == 2) CODECOMP_GLOAD(kstart + (t + 3) * kTileKeys, stage2)
-#endif
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       accA0 = mma_step<PASS>(qf[0][ks], ring[ks % RING], ks == 0 ? zero : accA0);
@@ -567,9 +530,6 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     CODECOMP_GLOAD(kstart + kTileKeys, stage)
     if constexpr (DEEP) CODECOMP_GLOAD(kstart + 2 * kTileKeys, stage2)
     lds_barrier();
-#ifdef CODECOMP_TRACE
-    mark_[1] = __builtin_amdgcn_s_memrealtime();
-#endif
 #pragma unroll
     for (int r = 0; r < RING; ++r) ring[r] = *kfrag_ptr(0, 0, r);
 
@@ -600,28 +560,18 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
       reduce_cols(ntiles - 3);
       tile_body(ntiles - 1, std::true_type{}, fast, a1, b1, stg_none{});
     }
-#ifdef CODECOMP_TRACE
-    mark_[2] = __builtin_amdgcn_s_memrealtime();
-#endif
 #pragma unroll
     for (int m = 0; m < MS; ++m) soft_step(accB0, accB1, m, b1, fast);
     soft_end(ntiles - 1, 1, b1, fast);
-#ifdef CODECOMP_TRACE
-    mark_[3] = __builtin_amdgcn_s_memrealtime();
-#endif
   };
 
   // The wave's flavour of the pipeline.  All flavours contain the same barriers in the same order.
   auto run_wave = [&](auto a1, auto b1) __attribute__((always_inline)) {
     if constexpr (PASS == 1) {
-#ifndef CODECOMP_PASS1_SAFE_ONLY
       run_chunk(std::true_type{}, a1, b1, std::false_type{});
       // a row that saw no key at all keeps the reference -1e30: its empty sum is 0, not a failure
       const bool bad = !(l_run0 <= 3.0e38f) || !(l_run1 <= 3.0e38f);     // inf or NaN: a logit outran the reference
       if (__syncthreads_or(bad)) run_chunk(std::false_type{}, a1, b1, std::true_type{});
-#else
-      run_chunk(std::false_type{}, a1, b1, std::false_type{});
-#endif
     } else {
       run_chunk(std::false_type{}, a1, b1, std::false_type{});
     }
@@ -658,82 +608,39 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   lds_barrier();
   x += ntiles;
   }   // segments
-#ifdef CODECOMP_TRACE     // one record per workgroup: where and when it ran
-  if (lane == 0 && PASS == 2) {
-    const int idx_ = blockIdx.x;
-    if (idx_ < 2048 && wave < 8) g_simd[idx_][wave] = (unsigned char)((__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 4) & 3);
-  }
-  if (tid == 0) {
-    const int idx_ = blockIdx.x;
-    if (idx_ < 2048) {
-      for (int q_ = 0; q_ < 4; ++q_) g_marks[PASS - 1][idx_][q_] = mark_[q_];
-
-      g_trace[PASS - 1][idx_][0] = rt0_;
-      g_trace[PASS - 1][idx_][1] = __builtin_amdgcn_s_memrealtime();
-      g_trace[PASS - 1][idx_][2] = __builtin_readcyclecounter() - clk0_;
-      g_trace[PASS - 1][idx_][3] = (long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) |
-                                   ((long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32);
-    }
-  }
-#endif
 #undef CODECOMP_GLOAD
-#undef CODECOMP_KEY0
 #undef CODECOMP_SSTORE
 }
 
 // Enqueues the row merge between the two passes (defined in score.hip).
 int launch_row_merge(const Plan& pl, const ScoreArgs& a, hipStream_t stream);
 
-#ifdef CODECOMP_TRACE
-// experiments: after the passes, write what the workgroups recorded (this translation unit's copy of the buffers)
-static void trace_dump() {
-  if (const char* path_ = getenv("CODECOMP_TRACE_OUT")) {
-    static long long host_[2][2048][4];
-    static unsigned char simd_[2048][8];
-    static long long marks_[2][2048][4];
-    hipDeviceSynchronize();
-    hipMemcpyFromSymbol(host_, HIP_SYMBOL(g_trace), sizeof(host_));
-    hipMemcpyFromSymbol(simd_, HIP_SYMBOL(g_simd), sizeof(simd_));
-    hipMemcpyFromSymbol(marks_, HIP_SYMBOL(g_marks), sizeof(marks_));
-    if (FILE* f_ = fopen(path_, "w")) {
-      const int nwg_ = 2048;
-      for (int p_ = 0; p_ < 2; ++p_)
-        for (int i_ = 0; i_ < nwg_ && i_ < 2048; ++i_)
-          if (host_[p_][i_][1] != 0) fprintf(f_, "T %d %d %d %lld %lld %lld %u %u\n", p_ + 1, i_, 0, host_[p_][i_][0],
-                  host_[p_][i_][1], host_[p_][i_][2], (unsigned)(host_[p_][i_][3] & 0xffffffff), (unsigned)(host_[p_][i_][3] >> 32));
-      for (int p_ = 0; p_ < 2; ++p_)
-        for (int i_ = 0; i_ < nwg_ && i_ < 2048; ++i_)
-          if (host_[p_][i_][1] != 0) fprintf(f_, "M %d %lld %lld %lld %lld %lld %lld\n", p_ + 1, host_[p_][i_][0], marks_[p_][i_][0], marks_[p_][i_][1],
-                  marks_[p_][i_][2], marks_[p_][i_][3], host_[p_][i_][1]);
-      for (int i_ = 0; i_ < 24; ++i_)
-        fprintf(f_, "S %d : %d %d %d %d %d %d %d %d\n", i_ * 7, simd_[i_ * 7][0], simd_[i_ * 7][1], simd_[i_ * 7][2], simd_[i_ * 7][3],
-                simd_[i_ * 7][4], simd_[i_ * 7][5], simd_[i_ * 7][6], simd_[i_ * 7][7]);
-      fclose(f_);
-    }
-  }
-}
-#endif
-
-// Workgroups that run at once on the current device: compute units x resident workgroups per unit.
+// Workgroups that run at once on the current device: compute units x resident workgroups per unit.  The answer
+// depends on the kernel and on the device, so every kernel keeps one cached value per device ordinal (the
+// occupancy query is a host-side calculation, but not a free one); 0 = not asked yet.  Two threads that ask at the
+// same time both compute the same number.  This cache is the only thing the library remembers between calls.
+constexpr int kMaxDevices = 64;
 template <class Kernel>
-int resident_workgroups(Kernel kernel, int threads) {
+int resident_workgroups(Kernel kernel, int threads, std::atomic<int>* cache) {
   int dev = 0, cus = 0, per_cu = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (dev >= 0 && dev < kMaxDevices) {
+    const int known = cache[dev].load(std::memory_order_relaxed);
+    if (known > 0) return known;
+  }
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess) return 0;
+  if (dev >= 0 && dev < kMaxDevices) cache[dev].store(cus * per_cu, std::memory_order_relaxed);
   return cus * per_cu;
 }
 
 // One launch "wave": as many workgroups as the device holds at once, each with an equal share of the
-// tiles (at least kMinTilesPerWorkgroup, so that small problems are not all prologue).
+// tiles (at least kMinTilesPerWorkgroup, so that small problems are not all prologue), unless the caller
+// fixed the number (codecomp_params.score_workgroups).
 inline int score_grid(const Plan& pl, int resident) {
   int g = resident > 0 ? resident : 256;
-  if (const char* e = getenv("CODECOMP_SCORE_WGS")) {        // experiments and tests: force the grid size
-    const int v = atoi(e);
-    if (v >= 1) g = v;
-  } else {
-    g = g < pl.real_tiles / kMinTilesPerWorkgroup ? g : pl.real_tiles / kMinTilesPerWorkgroup;
-  }
+  if (pl.grid_override > 0) g = pl.grid_override;
+  else g = g < pl.real_tiles / kMinTilesPerWorkgroup ? g : pl.real_tiles / kMinTilesPerWorkgroup;
   if (g > pl.real_tiles) g = pl.real_tiles;
   if (g > kMaxScoreGrid) g = kMaxScoreGrid;
   return g < 1 ? 1 : g;
@@ -741,11 +648,9 @@ inline int score_grid(const Plan& pl, int resident) {
 
 template <int D, int NW, bool K8>
 int launch_passes(const Plan& pl, ScoreArgs a, hipStream_t stream, unsigned stages) {
-  static const int resident1 = resident_workgroups(score_pass_kernel<D, NW, 1, false, K8>, NW * 64);
-  static const int resident2 = resident_workgroups(score_pass_kernel<D, NW, 2, false, K8>, NW * 64);
-  static const int resident2m = resident_workgroups(score_pass_kernel<D, NW, 2, true, K8>, NW * 64);
+  static std::atomic<int> cache1[kMaxDevices], cache2[kMaxDevices], cache2m[kMaxDevices];   // zero-initialised
   const dim3 block(NW * 64);
-  a.stat_wgs = score_grid(pl, resident1);
+  a.stat_wgs = score_grid(pl, resident_workgroups(score_pass_kernel<D, NW, 1, false, K8>, NW * 64, cache1));
   const bool any_tile = pl.real_tiles > 0;      // false: prefix-only softmax with no prefix anywhere
   if ((stages & CODECOMP_STAGE_ROW_STATS) && any_tile) {
     score_pass_kernel<D, NW, 1, false, K8><<<dim3(a.stat_wgs), block, 0, stream>>>(a);
@@ -755,40 +660,30 @@ int launch_passes(const Plan& pl, ScoreArgs a, hipStream_t stream, unsigned stag
     if (int rc = launch_row_merge(pl, a, stream)) return rc;
   }
   if ((stages & CODECOMP_STAGE_MASS) && any_tile) {
-    if (pl.variant & CODECOMP_VARIANT_GROUP_MAX)
-      score_pass_kernel<D, NW, 2, true, K8><<<dim3(score_grid(pl, resident2m)), block, 0, stream>>>(a);
-    else
-      score_pass_kernel<D, NW, 2, false, K8><<<dim3(score_grid(pl, resident2)), block, 0, stream>>>(a);
+    if (pl.variant & CODECOMP_VARIANT_GROUP_MAX) {
+      const int g = score_grid(pl, resident_workgroups(score_pass_kernel<D, NW, 2, true, K8>, NW * 64, cache2m));
+      score_pass_kernel<D, NW, 2, true, K8><<<dim3(g), block, 0, stream>>>(a);
+    } else {
+      const int g = score_grid(pl, resident_workgroups(score_pass_kernel<D, NW, 2, false, K8>, NW * 64, cache2));
+      score_pass_kernel<D, NW, 2, false, K8><<<dim3(g), block, 0, stream>>>(a);
+    }
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
   return 0;
-}
-
-template <int D, bool K8>
-int dispatch_waves_switch(const Plan& pl, const ScoreArgs& a, hipStream_t s, unsigned st) {
-  switch (pl.waves) {
-#ifndef CODECOMP_EXP_ONLY_8_WAVES     // experiments: a quick build with the kernels of the bench workload only
-    case 1: return launch_passes<D, 1, K8>(pl, a, s, st);
-    case 2: return launch_passes<D, 2, K8>(pl, a, s, st);
-    case 3: return launch_passes<D, 3, K8>(pl, a, s, st);
-    case 4: return launch_passes<D, 4, K8>(pl, a, s, st);
-    case 8: return launch_passes<D, 8, K8>(pl, a, s, st);
-#else
-    case 8: if constexpr (D == 128) return launch_passes<D, 8, K8>(pl, a, s, st);
-#endif
-  }
-  return CODECOMP_EINVAL_SHAPE;
 }
 
 // The passes of one (head_dim, key type) pair; each pair is instantiated in a translation unit of its own
 // (score_pass_*.hip) so that they compile side by side.
 template <int D, bool K8>
 int dispatch_waves(const Plan& pl, const ScoreArgs& a, hipStream_t s, unsigned st) {
-  const int rc = dispatch_waves_switch<D, K8>(pl, a, s, st);
-#ifdef CODECOMP_TRACE
-  if (rc == 0) trace_dump();
-#endif
-  return rc;
+  switch (pl.waves) {
+    case 1: return launch_passes<D, 1, K8>(pl, a, s, st);
+    case 2: return launch_passes<D, 2, K8>(pl, a, s, st);
+    case 3: return launch_passes<D, 3, K8>(pl, a, s, st);
+    case 4: return launch_passes<D, 4, K8>(pl, a, s, st);
+    case 8: return launch_passes<D, 8, K8>(pl, a, s, st);
+  }
+  return CODECOMP_EINVAL_SHAPE;
 }
 
 }  // namespace codecomp

@@ -37,8 +37,10 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_layout_matches_header():
-    # 10 x 4-byte fields, 4 pointers, 10 x int64 strides, span budget (float + int32), variant flags + kv_dtype
-    assert C.sizeof(b.codecomp_params) == 40 + 32 + 80 + 8 + 8
+    # 10 x 4-byte fields, 4 pointers, 10 x int64 strides, span budget (float + int32), variant flags + kv_dtype,
+    # the two launch-shape fields
+    assert C.sizeof(b.codecomp_params) == 40 + 32 + 80 + 8 + 8 + 8
+    assert b.codecomp_params.score_workgroups.offset == 168
     assert b.codecomp_params.score_variant.offset == 160
     assert b.codecomp_params.span_budget_ratio.offset == 152
     assert b.codecomp_params.cu_seqlens_host.offset == 40
@@ -67,6 +69,8 @@ def test_valid_params_and_workspace_size():
 
 @pytest.mark.parametrize("over,code", [
     (dict(n_layers=0), -2),
+    (dict(score_workgroups=-1), -2),
+    (dict(score_lead_tiles=65), -2),
     (dict(n_q_heads=7), -6),
     (dict(n_kv_heads=0), -6),
     (dict(head_dim=96), -7),

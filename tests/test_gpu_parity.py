@@ -22,7 +22,7 @@ def oracle_variant(flags: int) -> dict:
                 pool_domain="prefix" if flags & 16 else "row")
 
 
-def run_case(w, *, fused=True, check_oracle=True, variant=0, kv="bf16"):
+def run_case(w, *, fused=True, check_oracle=True, variant=0, kv="bf16", score_workgroups=0):
     """Runs the three steps (or the fused call) and compares every stage with the oracle.  kv = "fp8_e4m3":
     the cache (k and v) is the FP8 copy of the workload's bf16 cache."""
     import torch
@@ -30,7 +30,7 @@ def run_case(w, *, fused=True, check_oracle=True, variant=0, kv="bf16"):
     q, k, v, prior = wl.make_all(w)
     if kv == "fp8_e4m3":
         k, v = wl.bf16_bits_to_fp8_codes(k), wl.bf16_bits_to_fp8_codes(v)
-    prob = b.DeviceProblem(w, q, k, v, prior, score_variant=variant)
+    prob = b.DeviceProblem(w, q, k, v, prior, score_variant=variant, score_workgroups=score_workgroups)
     if fused:
         prob.compress()
     else:
@@ -88,8 +88,8 @@ def test_ragged_batch():
     run_case(w, fused=False)
 
 
-@pytest.mark.parametrize("wgs,lead", [(1, 4), (3, 0), (7, 4), (13, 9), (64, 1), (2048, 4), (2048, 40)])
-def test_any_split_of_the_tile_sequence_gives_the_same_scores(wgs, lead, monkeypatch):
+@pytest.mark.parametrize("wgs,lead", [(1, 4), (3, -1), (7, 4), (13, 9), (64, 1), (2048, 4), (2048, 40)])
+def test_any_split_of_the_tile_sequence_gives_the_same_scores(wgs, lead):
     """The score passes cut the tile sequence of all (layer, head, request) problems into one range per
     workgroup; a range may cover several problems, start inside one, or hold no tile at all.  Forced grid
     sizes and segment-start weights: the result must not depend on them (fp32 sums regroup: 1e-5)."""
@@ -103,9 +103,7 @@ def test_any_split_of_the_tile_sequence_gives_the_same_scores(wgs, lead, monkeyp
     sc_ref = ref.scores.cpu().numpy()
     cu = w.cu_seqlens()
     pu.assert_scores_close(sc_ref, orc.score_packed(q, k, prior, cu, pool_kernel=w.pool_kernel, prior_weight=w.prior_weight))
-    monkeypatch.setenv("CODECOMP_SCORE_WGS", str(wgs))
-    monkeypatch.setenv("CODECOMP_SCORE_LEAD_TILES", str(lead))
-    prob = b.DeviceProblem(w, q, k, v, prior)
+    prob = b.DeviceProblem(w, q, k, v, prior, score_workgroups=wgs, score_lead_tiles=lead)    # lead < 0: none
     prob.score()
     torch.cuda.synchronize()
     np.testing.assert_allclose(prob.scores.cpu().numpy(), sc_ref, rtol=1e-5, atol=1e-30)
@@ -334,18 +332,16 @@ def test_logits_that_outrun_the_first_tile_reference():
 
 @pytest.mark.parametrize("wgs", [0, 5, 61, 2048])
 @pytest.mark.parametrize("variant", [0, 8])
-def test_workgroups_enter_the_tile_sequence_anywhere(wgs, variant, monkeypatch):
+def test_workgroups_enter_the_tile_sequence_anywhere(wgs, variant):
     """More than 16 requests: a workgroup finds the request its range starts in with a cooperative search and then
     walks from request to request.  Forced grid sizes put the range starts anywhere (inside leads, on the last
     request, in the second problem); with the prefix-only softmax some requests have no tile at all."""
-    if wgs:
-        monkeypatch.setenv("CODECOMP_SCORE_WGS", str(wgs))
     rng = np.random.default_rng(77)
     lens = [int(x) for x in rng.choice([32, 33, 64, 100, 257, 900, 2100], size=45)]
     lens[7] = 32; lens[44] = 32                                       # nothing but the window (also as the last request)
     w = wl.scaled(wl.ragged_agentic(), n_layers=2, seqlens=lens, budgets=[max(32, n // 4) for n in lens], window=32,
                   n_kv_heads=2, n_q_heads=6)
-    run_case(w, variant=variant)
+    run_case(w, variant=variant, score_workgroups=wgs)
 
 
 def test_many_short_requests():
