@@ -61,15 +61,17 @@ def test_ragged_agentic_full():
     run_full(w, [(0, 0, shortest), (0, 2, longest), (0, 3, 5)])
 
 
-def test_llama8b_64k_two_layers():
-    w = wl.scaled(wl.llama8b_64k(), n_layers=2)
-    run_full(w, [(0, 0, 0), (1, 7, 0)])
+@pytest.mark.timeout(600)
+def test_llama8b_64k_all_layers():
+    # all 32 layers; the oracle scores sampled heads of the first, a middle and the last layer
+    run_full(wl.llama8b_64k(), [(0, 0, 0), (15, 4, 0), (31, 7, 0)])
 
 
-def test_long_128k_one_layer():
-    # W = 128, G = 7: 896 rows in two row splits, 64 chunks per head, budget partly forced by the prior
-    w = wl.scaled(wl.long_128k(), n_layers=1)
-    run_full(w, [(0, 1, 0)])
+@pytest.mark.timeout(600)
+def test_long_128k_all_layers():
+    # all 28 layers; W = 128, G = 7: 896 rows in two row splits, budget partly forced by the prior, the streaming
+    # form of the selection; the oracle scores one head of the first, a middle and the last layer
+    run_full(wl.long_128k(), [(0, 1, 0), (14, 3, 0), (27, 0, 0)])
 
 
 def test_qwen7b_32k_all_layers_fp8_cache():
