@@ -209,6 +209,21 @@ int codecomp_compress(const void* q_obs, const void* k, const void* v, const flo
                       const codecomp_params* params, float* scores, int32_t* idx, void* k_out, void* v_out,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* For callers that cannot allocate device memory or bring a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): codecomp_compress with the same kernels, arguments, outputs
+ * and errors, but without the workspace arguments.  The scratch memory lives in a device array inside the
+ * library, CODECOMP_STATIC_SCRATCH_BYTES per GPU, held from the library's first use of that GPU until the
+ * process ends; the call allocates and frees nothing.  Parameters whose codecomp_workspace_bytes() exceeds
+ * CODECOMP_STATIC_SCRATCH_BYTES are rejected with CODECOMP_EINVAL_WORKSPACE before anything is enqueued.  All
+ * calls on one GPU share that GPU's array (its contents are whatever the last call left; nothing needs to be
+ * cleared): two calls whose kernels may run at the same time on one GPU - different streams, different threads -
+ * race.  Calls on one stream, one after the other, are fine.  The first call on a device asks the runtime for
+ * the array's address on that device (hipGetSymbolAddress): make it outside a graph capture. */
+#define CODECOMP_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+int codecomp_compress_static(const void* q_obs, const void* k, const void* v, const float* prior,
+                             const codecomp_params* params, float* scores, int32_t* idx, void* k_out, void* v_out,
+                             void* hip_stream);
+
 /* Str. Score of section "Experiment": retained[l][h][r] = |{kept tokens j of request r : prior[j] > 0}| /
  * |{tokens j of request r : prior[j] > 0}| (NaN when the request has no such token).  `retained` is a
  * device f32 [n_layers][n_kv_heads][n_seqs]; idx as written by codecomp_select. */

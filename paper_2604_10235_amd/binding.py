@@ -86,6 +86,9 @@ def lib() -> C.CDLL:
         l.codecomp_compress.restype = C.c_int
         l.codecomp_compress.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, P, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        l.codecomp_compress_static.restype = C.c_int
+        l.codecomp_compress_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, P, C.c_void_p, C.c_void_p,
+                                               C.c_void_p, C.c_void_p, C.c_void_p]
         l.codecomp_structure_score.restype = C.c_int
         l.codecomp_structure_score.argtypes = [C.c_void_p, C.c_void_p, P, C.c_void_p, C.c_void_p]
         DP, IP = C.POINTER(C.c_double), C.POINTER(C.c_int32)
@@ -199,6 +202,14 @@ def codecomp_compress(q_obs, k, v, prior, params, scores, idx, k_out, v_out, wor
                                    workspace.numel() * workspace.element_size(), _stream()), "codecomp_compress")
 
 
+STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
+
+
+def codecomp_compress_static(q_obs, k, v, prior, params, scores, idx, k_out, v_out) -> None:
+    _check(lib().codecomp_compress_static(_ptr(q_obs), _ptr(k), _ptr(v), _ptr(prior), C.byref(params), _ptr(scores),
+                                          _ptr(idx), _ptr(k_out), _ptr(v_out), _stream()), "codecomp_compress_static")
+
+
 def codecomp_structure_score(idx, prior, params, retained) -> None:
     _check(lib().codecomp_structure_score(_ptr(idx), _ptr(prior), C.byref(params), _ptr(retained), _stream()),
            "codecomp_structure_score")
@@ -293,6 +304,10 @@ class DeviceProblem:
     def compress(self):
         codecomp_compress(self.q, self.k, self.v, self.prior, self.params, self.scores, self.idx, self.k_out,
                           self.v_out, self.workspace)
+
+    def compress_static(self):
+        codecomp_compress_static(self.q, self.k, self.v, self.prior, self.params, self.scores, self.idx, self.k_out,
+                                 self.v_out)
 
     @staticmethod
     def bits(t) -> np.ndarray:

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcodecomp.so")
 # the heavy translation units (the MFMA passes, one per head_dim and key type) first: they run side by side
 SOURCES = ["score_pass_d128_bf16.hip", "score_pass_d128_fp8.hip", "score_pass_d64_bf16.hip", "score_pass_d64_fp8.hip",
-           "api.hip", "score.hip", "select.hip", "gather.hip", "structure.hip"]
+           "api.hip", "score.hip", "select.hip", "gather.hip", "structure.hip", "static_scratch.hip"]
 # packed fp32 VALU ops are switched off on purpose (device pass only; the host pass ignores it)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"),
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

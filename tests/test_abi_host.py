@@ -132,6 +132,25 @@ def test_launching_calls_validate_before_touching_a_gpu():
     assert lib.codecomp_structure_score(None, fake, C.byref(p), fake, None) == -1
 
 
+def test_static_scratch_call_validates_on_the_host():
+    # the call without workspace arguments: same checks, and parameters that need more scratch than the library's
+    # device array holds are rejected before anything touches a GPU
+    from paper_2604_10235_amd import workloads as wl
+    lib = b.lib()
+    fake = 0x10000
+    assert lib.codecomp_compress_static(fake, fake, fake, fake, C.byref(good(head_dim=96)), fake, fake, fake, fake, None) == -7
+    assert lib.codecomp_compress_static(fake, fake, None, fake, C.byref(good()), fake, fake, fake, fake, None) == -1
+    assert lib.codecomp_compress_static(fake, fake + 4, fake, fake, C.byref(good()), fake, fake, fake, fake, None) == -2
+    w = wl.long_128k()
+    p = b.make_params(n_layers=w.n_layers, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                      window=w.window, pool_kernel=w.pool_kernel, prior_weight=w.prior_weight,
+                      cu_seqlens_host=w.cu_seqlens(), cu_budgets_host=w.cu_budgets(), cu_seqlens_dev=256, cu_budgets_dev=256)
+    assert b.codecomp_workspace_bytes(p) > b.STATIC_SCRATCH_BYTES
+    assert lib.codecomp_compress_static(fake, fake, fake, fake, C.byref(p), fake, fake, fake, fake, None) == -9
+    text = open(os.path.join(ROOT, "include", "codecomp.h")).read()
+    assert re.search(r"#define CODECOMP_STATIC_SCRATCH_BYTES \(32 \* 1024 \* 1024\)", text) and b.STATIC_SCRATCH_BYTES == 32 << 20
+
+
 def test_binding_raises_with_status_text():
     with pytest.raises(b.CodecompError) as e:
         b._check(-4, "codecomp_select")
