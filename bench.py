@@ -22,6 +22,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+# No transcendental rate is published.  v_exp_f32 issues at half the fma rate on gfx950 (measured, see
+# profiles/peaks_mi355x.md): 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz / 2.
+EXP_PEAK_PER_S = 256 * 4 * 16 * 2.4e9 / 2
 
 
 def algorithmic_bytes(w, kv_bytes: int = 2) -> dict:
@@ -41,20 +44,48 @@ def algorithmic_bytes(w, kv_bytes: int = 2) -> dict:
 
 
 def read_traffic(name: str):
-    """Measured HBM bytes per launch of the dominant kernel, from the committed counter summary
-    (profiles/pmc_<workload>.txt, lines `key = value`); None when no summary exists."""
+    """Measured HBM bytes per launch of the kernels, from the committed counter summary (profiles/pmc_<workload>.txt,
+    lines `key = value`; FETCH_SIZE / WRITE_SIZE cannot be read from inside this process); None when no summary
+    exists.  `commit` and `date` in that file say which build the counters were read on."""
     path = os.path.join(ROOT, "profiles", f"pmc_{name}.txt")
     if not os.path.exists(path):
         return None
-    vals = {}
+    vals = {"file": os.path.relpath(path, ROOT)}
     for line in open(path):
         if "=" in line and not line.lstrip().startswith("#"):
             k, v = line.split("=", 1)
+            v = v.strip()
             try:
                 vals[k.strip()] = float(v.split()[0])
-            except ValueError:
-                pass
-    return vals or None
+            except (ValueError, IndexError):
+                vals[k.strip()] = v
+    return vals
+
+
+def binding_roofline(flops_pass: float, logits_pass: float, ab: dict, k_bytes: int, ms_per_step: float, peaks):
+    """Floors of one step of the two-pass design (the logits are formed twice: row normalisers, then column sums) at
+    the published peaks and, when measured, at what this GPU sustained in this run.  hbm_one_read is the method's own
+    traffic (K once); hbm_two_reads adds K's second read.  issue_mix is the measured instruction mix of the passes
+    without memory (MFMA and softmax VALU work compete for issue slots).  frac = largest floor / time per step."""
+    def floors(mfma_tflops, exp_per_s, hbm_gbs, mix_logits_per_s=None):
+        f = {"mfma_two_passes": 2 * flops_pass / (mfma_tflops * 1e12) * 1e3,
+             "exp_two_passes": 2 * logits_pass / exp_per_s * 1e3,
+             "hbm_one_read": ab["total"] / (hbm_gbs * 1e9) * 1e3,
+             "hbm_two_reads": (ab["total"] + k_bytes) / (hbm_gbs * 1e9) * 1e3}
+        if mix_logits_per_s:
+            f["issue_mix_two_passes"] = 2 * logits_pass / mix_logits_per_s * 1e3
+        return f
+
+    def pack(f):
+        binding = max((k for k in f if k != "hbm_one_read"), key=lambda k: f[k])
+        return {"floors_ms": {k: round(v, 4) for k, v in f.items()}, "binding": binding,
+                "frac": round(f[binding] / ms_per_step, 4)}
+
+    out = {"spec": pack(floors(MFMA_BF16_PEAK_TFLOPS, EXP_PEAK_PER_S, HBM_PEAK_GBS))}
+    if peaks:
+        out["measured"] = pack(floors(peaks["mfma_bf16_tflops"], peaks["exp_per_s"], peaks["read_gb_per_s"],
+                                      peaks["mix_logits_per_s"]))
+    return out
 
 
 def main() -> int:
@@ -66,8 +97,11 @@ def main() -> int:
     ap.add_argument("--workload", default="qwen7b_32k")
     ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8_e4m3"],
                     help="storage type of the KV cache (the headline workload is bf16; fp8_e4m3 is the 8-bit variant)")
-    ap.add_argument("--cpu-layers", type=int, default=28, help="layers the CPU oracle is timed and compared on")
+    ap.add_argument("--cpu-layers", type=int, default=0,
+                    help="layers the CPU oracle is timed and compared on (always layer 0 and the last one); 0 = as many "
+                         "as keep its matrix products under 1.5 TFLOP (all 28 of the bench workload: ~5 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the micro-benchmarks of what the GPU sustains")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (experiments only)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of 1 GiB (reads 1 GiB, writes 1 GiB): the reference "
@@ -107,11 +141,17 @@ def main() -> int:
     for _ in range(args.warmup):
         prob.compress()
     torch.cuda.synchronize()
+    # the timed region: K fused calls back to back, bracketed by two events on the stream the kernels run on
+    # (torch's current stream) and, outside them, by the host clock around a synchronisation
+    ev_begin, ev_end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev_begin.record()
     for _ in range(args.steps):
         prob.compress()
+    ev_end.record()
     torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step_host = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = ev_begin.elapsed_time(ev_end) / args.steps
 
     # per-kernel durations: the same kernels enqueued one by one with events between them, all steps
     # back to back like the fused loop above (one synchronisation at the end: same clocks, same heat)
@@ -147,13 +187,22 @@ def main() -> int:
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": None if not traffic else traffic.get(f"{dom}_hbm_bytes_per_launch"),
+                "traffic_source": None if not traffic else {k_: traffic.get(k_) for k_ in ("file", "commit", "date")},
                 "kernel_ms": round(stage_ms[dom], 4), "flop_per_launch": flops}
+    peaks_now = None
+    if not args.no_peaks:
+        from paper_2604_10235_amd import peaks
+        peaks.measure()                           # the first measurement also pays for the set-up
+        peaks_now = peaks.measure()
+        peaks.release()
+    logits = float(w.group * w.window * T * w.n_kv_heads * L)
 
     out = {
         "metric": "KV tokens scored+selected+gathered/sec per GPU; HBM GB/s as % of peak",
         "value": round(value, 1), "unit": "token-layers/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "ms_per_step_host": round(ms_per_step_host, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.kv_dtype, "data": "synthetic",
         "config": {"workload": w.name if args.kv_dtype == "bf16" else f"{w.name} with an {args.kv_dtype} cache", "n_layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "tokens": T, "n_seqs": w.n_seqs, "window": w.window,
                    "budget_total": w.total_budget, "pool_kernel": w.pool_kernel, "prior_weight": w.prior_weight},
@@ -163,6 +212,9 @@ def main() -> int:
         "stage_ms": {k_: round(v_, 4) for k_, v_ in stage_ms.items()},
         "stage_ms_sum": round(sum(stage_ms.values()), 4),
         "roofline": roofline,
+        "binding_roofline": binding_roofline(flops, logits, ab, ab["k_read"], ms_per_step, peaks_now),
+        "peaks": {"spec": {"mfma_bf16_tflops": MFMA_BF16_PEAK_TFLOPS, "hbm_gb_per_s": HBM_PEAK_GBS,
+                           "exp_per_s": EXP_PEAK_PER_S}, "measured": peaks_now},
         "input_generation_s": round(t_gen, 1),
     }
 
@@ -171,19 +223,23 @@ def main() -> int:
         from tests import parity_util as pu
         try:
             from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+            blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
-            cores = os.cpu_count() or 1
-        nl = max(1, min(args.cpu_layers, L))
+            blas_threads = None
+        auto = int(1.5e12 // max(1.0, flops / L))
+        nl = max(1, min(args.cpu_layers if args.cpu_layers > 0 else max(2, auto), L))
         layers = sorted(set(np.linspace(0, L - 1, nl).round().astype(int).tolist()))   # always layer 0 and L-1
         cu, cb = w.cu_seqlens(), w.cu_budgets()
-        t0 = time.perf_counter()
+        t0, c0 = time.perf_counter(), time.process_time()
         sc_ref, idx_ref, ko_ref, vo_ref = orc.compress_packed(q[layers], k[layers], v[layers], prior, cu, cb,
                                                              window=w.window, pool_kernel=w.pool_kernel,
                                                              prior_weight=w.prior_weight, k_format=args.kv_dtype)
-        t_cpu = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(T * len(layers) / t_cpu, 1), "unit": "token-layers/s", "cores": cores,
-                               "kind": "oracle", "seconds": round(t_cpu, 2),
+        t_cpu, c_cpu = time.perf_counter() - t0, time.process_time() - c0
+        # cores = CPU time / wall time of the oracle run: only its matrix products run on the BLAS thread pool, the
+        # exponentials, sums and sorts are single-threaded numpy
+        out["cpu_baseline"] = {"value": round(T * len(layers) / t_cpu, 1), "unit": "token-layers/s",
+                               "cores": max(1, round(c_cpu / t_cpu)), "cpu_seconds": round(c_cpu, 2),
+                               "blas_threads": blas_threads, "kind": "oracle", "seconds": round(t_cpu, 2),
                                "sample": f"{len(layers)} of {L} layers (all heads, all requests) of the same inputs"}
         # parity report on the sampled layers (the GPU results are those of the timed fused call)
         prob.compress(); torch.cuda.synchronize()

@@ -1,0 +1,222 @@
+// libcodecomp_peaks: what this GPU sustains on the ingredients of the score passes, measured with HIP events.
+// Not part of the hot path: bench.py prints these rates next to the published peaks, so that the roofline
+// fractions can be read against both.  Five short kernels, each launched twice (the second launch is timed):
+//   mfma   v_mfma_f32_32x32x16_bf16 only, operands = random bf16 numbers (N(0,1), from the caller's buffer):
+//          constant operands flip no bits in the multipliers and run ~25 % faster at the power limit
+//   exp    v_exp_f32 only (16 independent chains per lane)
+//   fma    v_fma_f32 only (16 independent chains per lane)
+//   mix    the steady-state instruction mix of a score pass without memory: per MFMA two logits per lane, each
+//          (fma, exp2, add), interleaved one MFMA : 2 x 3 VALU - the issue-bound floor of a pass
+//   copy   16-byte loads and stores, one pass over `bytes` bytes (read + write), and a read-only pass
+// plus the shader clock under the mfma and mix loads (one wave's shader-cycle counter against its 100 MHz
+// real-time counter).  The mfma and mix kernels are launched with exactly as many workgroups as the device holds at
+// once, two waves per SIMD where they fit (the score passes run two per SIMD).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+#define BC(a) __builtin_bit_cast(bf16x8, a)
+
+extern "C" {
+typedef struct codecomp_peaks {
+  double mfma_bf16_tflops;      /* dense bf16 MFMA, random operands                                   */
+  double mfma_clock_mhz;        /* shader clock during that run                                       */
+  double exp_per_s;             /* v_exp_f32 results per second, whole chip                           */
+  double fma_per_s;             /* v_fma_f32 results per second, whole chip                           */
+  double mix_logits_per_s;      /* logits per second through (half an MFMA at d = 128) + fma + exp2 + add */
+  double mix_clock_mhz;
+  double copy_gbs;              /* (bytes read + bytes written) / time of the copy pass               */
+  double read_gbs;              /* bytes read / time of the read-only pass                            */
+  double mix_cycles_per_mfma;   /* shader cycles a SIMD spends per MFMA (with its two logits of softmax work per lane) */
+  int32_t mix_waves_per_simd;
+  int32_t compute_units;
+  int32_t status;               /* 0 or the hipError_t that stopped the measurement                   */
+  int32_t pad_;
+} codecomp_peaks;
+}
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__global__ __launch_bounds__(kThreads) void mfma_kernel(const u32x4* __restrict__ rnd, float* out, long long* clk, int iters) {
+  // 12 operand fragments per lane, all different random numbers
+  u32x4 a[8], b[4];
+  const int lane = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = rnd[(i * kThreads + lane) & 4095];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b[i] = rnd[((8 + i) * kThreads + lane) & 4095];
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc[i] = f32x16{0};
+  const long long t0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(BC(a[(ks + c) & 7]), BC(b[(ks + it + c) & 3]), acc[c], 0, 0, 0);
+  }
+  const long long t1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) s += acc[c][0] + acc[c][7];
+  if (s == 12345.678f) out[0] = s;                   // keeps the accumulators alive; practically never true
+  if (blockIdx.x == 0 && threadIdx.x == 0) { clk[0] = t1 - t0; clk[1] = r1 - r0; }
+}
+
+template <int KIND>   // 0: exp2, 1: fma
+__global__ __launch_bounds__(kThreads) void valu_kernel(float* out, int iters, float seed) {
+  float x[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) x[i] = seed * (float)(threadIdx.x % 7 + i + 1) * 0.01f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if (KIND == 0) x[i] = __builtin_amdgcn_exp2f(-x[i]);           // stays in (0.5, 1]
+      else x[i] = __builtin_fmaf(x[i], 0.999f, seed);                // stays bounded
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += x[i];
+  if (s == 12345.678f) out[0] = s;
+}
+
+// One "tile" = 64 keys for two row blocks of 32 rows: 2 phases x (8 k-steps x 2 MFMAs), and per phase the 32 logits
+// a lane holds of the previous phase go through fma, exp2, add (two per MFMA).
+__global__ __launch_bounds__(kThreads) void mix_kernel(const u32x4* __restrict__ rnd, float* out, long long* clk, int tiles, float seed) {
+  u32x4 a[8], b[4];
+  const int lane = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = rnd[(i * kThreads + lane) & 4095];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b[i] = rnd[((8 + i) * kThreads + lane) & 4095];
+  f32x16 accA0 = {0}, accA1 = {0}, accB0 = {0}, accB1 = {0};
+  float nl[2][16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) { nl[0][v] = -30.f - v * seed; nl[1][v] = -31.f - v * seed; }
+  float tot = 0.f;
+  const float c = 0.1275f;
+  const f32x16 zero = {0};
+  const long long t0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
+  for (int t = 0; t < tiles; ++t) {
+#pragma unroll
+    for (int ph = 0; ph < 2; ++ph) {
+      f32x16& n0 = ph == 0 ? accA0 : accB0; f32x16& n1 = ph == 0 ? accA1 : accB1;
+      const f32x16& p0 = ph == 0 ? accB0 : accA0; const f32x16& p1 = ph == 0 ? accB1 : accA1;
+      float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(BC(a[ks]), BC(b[(ks + t) & 3]), ks == 0 ? zero : n0, 0, 0, 0);
+        s0 += __builtin_amdgcn_exp2f(__builtin_fmaf(p0[ks], c, nl[0][ks]));
+        s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(p1[ks], c, nl[1][ks]));
+        n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(BC(a[7 - ks]), BC(b[(ks + t + 2) & 3]), ks == 0 ? zero : n1, 0, 0, 0);
+        s0 += __builtin_amdgcn_exp2f(__builtin_fmaf(p0[ks + 8], c, nl[0][ks + 8]));
+        s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(p1[ks + 8], c, nl[1][ks + 8]));
+      }
+#pragma unroll
+      for (int m = 0; m < 16; ++m) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+      }
+      tot += s0 + s1;
+    }
+  }
+  const long long t1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+  const float s = tot + accA0[0] + accA1[3] + accB0[5] + accB1[7];
+  if (s == 12345.678f) out[0] = s;
+  if (blockIdx.x == 0 && threadIdx.x == 0) { clk[0] = t1 - t0; clk[1] = r1 - r0; }
+}
+
+__global__ __launch_bounds__(kThreads) void copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(kThreads) void read_kernel(const u32x4* __restrict__ src, unsigned* out, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  unsigned acc = 0;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += stride) {
+    const u32x4 v = src[i];
+    acc ^= v.x ^ v.y ^ v.z ^ v.w;
+  }
+  if (acc == 0x12345678u) out[0] = acc;
+}
+
+}  // namespace
+
+// rnd: device, >= 64 KiB of bf16 bit patterns of random numbers (operands of the MFMA runs), 16-byte aligned.
+// buf_a, buf_b: device, `bytes` bytes each (copy source and destination; bytes a multiple of 16, several times the
+// 256 MB memory-side cache for a figure that means HBM).  small: device, >= 64 bytes (sink and cycle counts).
+// Synchronises the stream (this is a measurement, not a hot-path call).  Returns 0 or a hipError_t.
+extern "C" int codecomp_measure_peaks(const void* rnd, void* buf_a, void* buf_b, size_t bytes, void* small,
+                                      codecomp_peaks* out, void* hip_stream) {
+  if (!rnd || !buf_a || !buf_b || !small || !out || bytes < (1u << 20) || (bytes & 15)) return -1;
+  hipStream_t s = (hipStream_t)hip_stream;
+  int dev = 0, cus = 0;
+  hipError_t e;
+  if ((e = hipGetDevice(&dev)) || (e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev))) return out->status = (int)e;
+  hipEvent_t e0, e1;
+  if ((e = hipEventCreate(&e0)) || (e = hipEventCreate(&e1))) return out->status = (int)e;
+  float* sink = static_cast<float*>(small);
+  long long* clk = reinterpret_cast<long long*>(static_cast<char*>(small) + 32);
+  const u32x4* r = static_cast<const u32x4*>(rnd);
+  float ms = 0.f;
+  long long cyc[2] = {0, 0};
+  int occ_mfma = 0, occ_mix = 0;
+  if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_mfma, mfma_kernel, kThreads, 0)) ||
+      (e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_mix, mix_kernel, kThreads, 0))) return out->status = (int)e;
+  if (occ_mfma < 1 || occ_mix < 1) return out->status = -2;
+  const int grid = cus * 2;                      // the plain VALU kernels: small, any number fits
+  auto timed = [&](auto launch) -> int {
+    launch();                                    // warm-up: clocks, code load
+    if ((e = hipEventRecord(e0, s))) return (int)e;
+    launch();
+    if ((e = hipEventRecord(e1, s)) || (e = hipEventSynchronize(e1)) || (e = hipGetLastError())) return (int)e;
+    return (int)hipEventElapsedTime(&ms, e0, e1);
+  };
+  int rc = 0;
+  out->compute_units = cus;
+  {
+    const int iters = 6000;                      // ~ 8 ms
+    const int g = cus * (occ_mfma < 2 ? occ_mfma : 2);
+    if ((rc = timed([&] { mfma_kernel<<<g, kThreads, 0, s>>>(r, sink, clk, iters); }))) goto done;
+    (void)hipMemcpyAsync(cyc, clk, 16, hipMemcpyDeviceToHost, s); (void)hipStreamSynchronize(s);
+    const double flop = (double)g * (kThreads / 64) * iters * 32.0 * 32768.0;
+    out->mfma_bf16_tflops = flop / (ms * 1e-3) / 1e12;
+    out->mfma_clock_mhz = cyc[1] > 0 ? (double)cyc[0] / ((double)cyc[1] * 1e-8) / 1e6 : 0.0;
+  }
+  {
+    const int iters = 20000;
+    if ((rc = timed([&] { valu_kernel<0><<<grid * 2, kThreads, 0, s>>>(sink, iters, 0.3f); }))) goto done;
+    out->exp_per_s = (double)grid * 2 * kThreads * iters * 16.0 / (ms * 1e-3);
+    if ((rc = timed([&] { valu_kernel<1><<<grid * 2, kThreads, 0, s>>>(sink, iters, 0.3f); }))) goto done;
+    out->fma_per_s = (double)grid * 2 * kThreads * iters * 16.0 / (ms * 1e-3);
+  }
+  {
+    const int tiles = 4000;
+    const int g = cus * (occ_mix < 2 ? occ_mix : 2);
+    out->mix_waves_per_simd = occ_mix < 2 ? occ_mix : 2;
+    if ((rc = timed([&] { mix_kernel<<<g, kThreads, 0, s>>>(r, sink, clk, tiles, 0.3f); }))) goto done;
+    (void)hipMemcpyAsync(cyc, clk, 16, hipMemcpyDeviceToHost, s); (void)hipStreamSynchronize(s);
+    out->mix_logits_per_s = (double)g * (kThreads / 64) * tiles * 64.0 * 64.0 / (ms * 1e-3);   // 64 keys x 64 rows per wave and tile
+    out->mix_clock_mhz = cyc[1] > 0 ? (double)cyc[0] / ((double)cyc[1] * 1e-8) / 1e6 : 0.0;
+    out->mix_cycles_per_mfma = (double)cyc[0] / tiles / 32.0 * out->mix_waves_per_simd;          // shader cycles per MFMA slot of a SIMD
+  }
+  {
+    const size_t n16 = bytes / 16;
+    if ((rc = timed([&] { copy_kernel<<<cus * 8, kThreads, 0, s>>>(static_cast<const u32x4*>(buf_a), static_cast<u32x4*>(buf_b), n16); }))) goto done;
+    out->copy_gbs = 2.0 * (double)bytes / (ms * 1e-3) / 1e9;
+    if ((rc = timed([&] { read_kernel<<<cus * 8, kThreads, 0, s>>>(static_cast<const u32x4*>(buf_a), reinterpret_cast<unsigned*>(sink), n16); }))) goto done;
+    out->read_gbs = (double)bytes / (ms * 1e-3) / 1e9;
+  }
+done:
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  return out->status = rc;
+}
