@@ -88,6 +88,33 @@ def binding_roofline(flops_pass: float, logits_pass: float, ab: dict, k_bytes: i
     return out
 
 
+class LayerSlices:
+    """The same device buffers, worked through in slices of consecutive layers: every call of the path is made once
+    per slice, one slice after the other (row statistics -> merge -> mass -> finish -> select -> gather of a slice
+    before the next slice starts), so that the second logit pass of a slice reads the K its first pass has just
+    read.  An experiment on K's second read (--layer-slices); argument marshalling only."""
+
+    def __init__(self, prob, binding, n_slices: int):
+        w = prob.w
+        L = prob.n_layers
+        if n_slices < 1 or L % n_slices:
+            raise ValueError(f"--layer-slices must divide the layer count {L}")
+        per = L // n_slices
+        self.b, self.prob, self.subs = binding, prob, []
+        for s in range(n_slices):
+            sl = slice(s * per, (s + 1) * per)
+            p = binding.make_params(n_layers=per, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                                    window=w.window, pool_kernel=w.pool_kernel, prior_weight=w.prior_weight,
+                                    cu_seqlens_host=w.cu_seqlens(), cu_budgets_host=w.cu_budgets(),
+                                    cu_seqlens_dev=prob.cu_seqlens.data_ptr(), cu_budgets_dev=prob.cu_budgets.data_ptr(),
+                                    kv_dtype=prob.params.kv_dtype)
+            self.subs.append((p, prob.q[sl], prob.k[sl], prob.v[sl], prob.scores[sl], prob.idx[sl], prob.k_out[sl], prob.v_out[sl]))
+
+    def compress(self):
+        for p, q, k, v, sc, ix, ko, vo in self.subs:
+            self.b.codecomp_compress(q, k, v, self.prob.prior, p, sc, ix, ko, vo, self.prob.workspace)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -103,6 +130,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peaks", action="store_true", help="skip the micro-benchmarks of what the GPU sustains")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (experiments only)")
+    ap.add_argument("--layer-slices", type=int, default=1,
+                    help="experiment on K's second read: run the whole path slice by slice over this many slices of "
+                         "consecutive layers (1 = all layers in one call, the product's way); only the fused loop is timed")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of 1 GiB (reads 1 GiB, writes 1 GiB): the reference "
                          "dispatch for scaling FETCH_SIZE / WRITE_SIZE counter readings")
@@ -137,6 +167,24 @@ def main() -> int:
     t_gen = time.time() - t0
     prob = binding.DeviceProblem(w, q, k, v, prior)
     torch.cuda.synchronize()
+    if args.layer_slices > 1:
+        sliced = LayerSlices(prob, binding, args.layer_slices)
+        for _ in range(args.warmup):
+            sliced.compress()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(args.steps):
+            sliced.compress()
+        ev1.record()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (prob.idx, prob.k_out, prob.v_out)]
+        prob.compress(); torch.cuda.synchronize()
+        same = all(torch.equal(a_, b_) for a_, b_ in zip(got, (prob.idx, prob.k_out, prob.v_out)))
+        print(json.dumps({"experiment": "layer slices", "workload": w.name, "layer_slices": args.layer_slices,
+                          "layers_per_slice": w.n_layers // args.layer_slices, "steps": args.steps,
+                          "ms_per_step": round(ev0.elapsed_time(ev1) / args.steps, 4),
+                          "outputs_equal_the_unsliced_call": bool(same)}))
+        return 0 if same else 4
 
     for _ in range(args.warmup):
         prob.compress()
