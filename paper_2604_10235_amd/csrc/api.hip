@@ -131,8 +131,8 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   const int64_t positions = tiles + (int64_t)pl->lead_tiles * pl->n_seqs;
   if (positions * problems > (1 << 30)) return CODECOMP_EINVAL_SHAPE;
   pl->tiles_per_problem = (int)positions;
-  pl->total_tiles = (int)(positions * problems);
-  pl->real_tiles = (int)(tiles * problems);
+  pl->total_tiles = (int)(positions * pl->L * pl->Hkv);      // the row splits of a problem walk the same positions
+  pl->real_tiles = (int)(tiles * pl->L * pl->Hkv);
 
   const int64_t d = pl->d;
   pl->q_st = p->q_stride_tok ? p->q_stride_tok : d;
@@ -154,7 +154,7 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   const size_t LH = (size_t)pl->L * pl->Hkv;
   const size_t lpad = (size_t)pl->row_splits * pl->row_blocks * 32;        // normaliser rows
   size_t off = 0;
-  // one statistics slot per segment; slot numbers stay below (workgroups + problems)
+  // one statistics slot per segment and row split; slot numbers stay below (teams + problems) * row_splits
   const size_t slots = (size_t)kMaxScoreGrid + LH * pl->row_splits * pl->n_seqs;
   pl->off_stats = off; off = align256(off + slots * (pl->waves * kRowsPerWave) * 2 * sizeof(float));
   pl->off_lse = off;   off = align256(off + LH * pl->n_seqs * lpad * sizeof(float));

@@ -37,8 +37,8 @@ struct Plan {
   uint8_t rb_holder[2 * kMaxWaves][2];   // per row block: wave * 2 + slot of its (one or two) owners, 255 = none
   int grid_override;         // > 0: the caller fixed the number of workgroups of the score passes
   int lead_tiles;            // empty positions before each request's tiles in the sequence below: the cost of starting a segment
-  int tiles_per_problem;     // sum over requests of (lead_tiles + ceil(N_r / kTileKeys)): positions of one (layer, head, row split)
-  int total_tiles;           // L * Hkv * row_splits * tiles_per_problem, shared out evenly over the workgroups
+  int tiles_per_problem;     // sum over requests of (lead_tiles + ceil(N_r / kTileKeys)): positions of one (layer, head)
+  int total_tiles;           // L * Hkv * tiles_per_problem, shared out evenly over the teams of row_splits workgroups
   int real_tiles;            // the same without the leads
   int64_t q_sl, q_ss, q_sh, q_st;
   int64_t kv_sl, kv_sh, kv_st;

@@ -10,7 +10,7 @@ extern template int dispatch_waves<128, true>(const Plan&, const ScoreArgs&, hip
 extern template int dispatch_waves<64, false>(const Plan&, const ScoreArgs&, hipStream_t, unsigned);
 extern template int dispatch_waves<64, true>(const Plan&, const ScoreArgs&, hipStream_t, unsigned);
 
-// One thread per (layer*head, request, row): log2-sum-exp over the segments that cover the request and
+// One thread per (layer*head, request, row): log2-sum-exp over the segments (of the teams) that cover the request and
 // over the (at most two) wave slots that hold a share of the row's keys.
 __global__ __launch_bounds__(256) void score_merge_kernel(ScoreArgs a) {
   __shared__ int part[256 / 64];
@@ -29,22 +29,23 @@ __global__ __launch_bounds__(256) void score_merge_kernel(ScoreArgs a) {
   if (row >= a.lrows) return;
   const int split = row / (a.nb * 32);
   const int rb = (row - split * a.nb * 32) >> 5;
-  const int hi = lz * a.row_splits + split;
   const int nt = (a.cu_seqlens[seq + 1] - a.cu_seqlens[seq] - a.key_trim + kTileKeys - 1) / kTileKeys;
   if (nt == 0) {                           // no key to attend to: nothing reads this normaliser
     a.lse[((int64_t)lz * a.n_seqs + seq) * a.lrows + row] = 0.f;
     return;
   }
-  const int x0 = hi * a.tiles_per_problem + tile_off;
-  const int g0 = wg_of_tile(x0, a.total_tiles, a.stat_wgs), g1 = wg_of_tile(x0 + nt - 1, a.total_tiles, a.stat_wgs);
-  const int p = hi * a.n_seqs + seq;
+  const int x0 = lz * a.tiles_per_problem + tile_off;
+  const int g0 = wg_of_tile(x0, a.total_tiles, a.stat_teams), g1 = wg_of_tile(x0 + nt - 1, a.total_tiles, a.stat_teams);
+  const int p = lz * a.n_seqs + seq;
   float M = NEG_BIG, L = 0.f;
   for (int h = 0; h < 2; ++h) {
     const int holder = a.rb_holder[rb][h];
     if (holder == 255) continue;
-    const float* sh = a.stats + ((int64_t)p * a.srows + holder * 32 + (row & 31)) * 2;
+    // the segment of team g in this problem and row split sits in slot (g + p) * row_splits + split
+    const float* sh = a.stats + (((int64_t)p * a.row_splits + split) * a.srows + holder * 32 + (row & 31)) * 2;
     for (int g = g0; g <= g1; ++g) {
-      const float m = sh[(int64_t)g * a.srows * 2], l = sh[(int64_t)g * a.srows * 2 + 1];
+      const int64_t at = (int64_t)g * a.row_splits * a.srows * 2;
+      const float m = sh[at], l = sh[at + 1];
       const float Mn = fmaxf(M, m);
       L = L * __builtin_amdgcn_exp2f(M - Mn) + l * __builtin_amdgcn_exp2f(m - Mn);
       M = Mn;
@@ -172,7 +173,7 @@ int launch_score(const Plan& pl, const void* q, const void* k, const float* prio
   a.lrows = pl.row_splits * pl.row_blocks * 32;
   for (int w = 0; w < kMaxWaves; ++w) a.wave_desc[w] = pl.wave_desc[w];
   for (int b = 0; b < 2 * kMaxWaves; ++b) { a.rb_holder[b][0] = pl.rb_holder[b][0]; a.rb_holder[b][1] = pl.rb_holder[b][1]; }
-  a.lead = pl.lead_tiles; a.tiles_per_problem = pl.tiles_per_problem; a.total_tiles = pl.total_tiles; a.stat_wgs = 0; a.T = pl.T;
+  a.lead = pl.lead_tiles; a.tiles_per_problem = pl.tiles_per_problem; a.total_tiles = pl.total_tiles; a.stat_teams = 0; a.T = pl.T;
   a.LH = pl.L * pl.Hkv;
   a.q_sl = pl.q_sl; a.q_ss = pl.q_ss; a.q_sh = pl.q_sh; a.q_st = pl.q_st;
   a.kv_sl = pl.kv_sl; a.kv_sh = pl.kv_sh; a.kv_st = pl.kv_st;

@@ -43,17 +43,21 @@ struct ScoreArgs {
   float* lse;     // [L*Hkv][n_seqs][lrows]         : log2 sum_j exp2(s_j * c), lrows = row_splits * nb * 32
   float* uraw;    // [row_splits][L*Hkv][T]         : (1/G) * sum over this split's rows of A
   int n_seqs, Hkv, LH, G, W, R, row_splits, nb, srows, lrows, T;
-  // Work distribution.  The 64-key tiles of all problems (layer*head, row split, request), in that order,
-  // form one sequence; workgroup g of `wgs` takes positions [g*total/wgs, (g+1)*total/wgs) and walks
-  // through the "segments" in which that range meets the problems.  Every problem is preceded by
+  // Work distribution.  The 64-key tiles of all problems (layer*head, request), in that order, form one
+  // sequence.  The workgroups of a launch form teams of row_splits members (one per row split; a team of one
+  // when all rows fit one workgroup); team q of `teams` takes positions [q*total/teams, (q+1)*total/teams) and
+  // every member walks through the "segments" in which that range meets the problems, for its own rows.  The
+  // members of a team run on the same accelerator die and stream the same keys at the same time, so that all
+  // but the first of them find a K tile in that die's L2.  Every problem is preceded by
   // `lead` empty positions: starting a segment costs about that many tiles (query fragments, first K
   // tile), so a range that crosses into a new problem gets that many tiles less, and all workgroups
-  // finish together.  Pass 1 leaves the statistics of the segment of workgroup g in problem p in slot
-  // g + p (distinct for distinct segments).
+  // finish together.  Pass 1 leaves the statistics of the segment of team q in problem p = layer*head * n_seqs +
+  // request, row split s, in slot (q + p) * row_splits + s (distinct for distinct segments: along the sequence
+  // neither q nor p decreases and one of them grows from one segment to the next).
   int lead;                          // empty positions before the tiles of each problem
   int tiles_per_problem;             // sum over requests of (lead + ceil(N_r / 64))
-  int total_tiles;                   // L*Hkv * row_splits * tiles_per_problem
-  int stat_wgs;                      // workgroups of the pass-1 launch whose statistics `stats` holds
+  int total_tiles;                   // L*Hkv * tiles_per_problem
+  int stat_teams;                    // teams of the pass-1 launch whose statistics `stats` holds
   int key_trim;                      // keys at the end of every request left out of the softmax (prefix-only variant)
   int blocks_per_head;               // largest-head-mass variant: row blocks of one query head (window / 32)
   uint32_t wave_desc[kMaxWaves];     // row block of slot 0 | row block of slot 1 << 8 | halves of slot 1 << 16 (bit 0: first, bit 1: second)
@@ -125,9 +129,24 @@ __device__ __forceinline__ void locate_first(const int32_t* cu, int n_seqs, int 
   }
 }
 
-// Workgroup (of `wgs`) whose tile range [g*total/wgs, (g+1)*total/wgs) holds tile x.
+// Team (of `wgs`) whose tile range [g*total/wgs, (g+1)*total/wgs) holds tile x.
 __device__ __forceinline__ int wg_of_tile(int x, int total, int wgs) {
   return (int)((((int64_t)x + 1) * wgs + total - 1) / total) - 1;
+}
+
+// Team and row split of workgroup b in a launch of `grid` workgroups (grid = teams * row_splits).  Workgroups are
+// handed to the eight accelerator dies in turn (b % 8), so the members of a team are 8 apart wherever the number of
+// teams allows it: they then share a die, and its L2.
+__host__ __device__ __forceinline__ void team_of(int b, int grid, int row_splits, int& team, int& split) {
+  if (row_splits == 1) { team = b; split = 0; return; }
+  if (grid % (8 * row_splits) == 0) {
+    const int die = b & 7, t = b >> 3;
+    team = 8 * (t / row_splits) + die;
+    split = t % row_splits;
+  } else {
+    team = b / row_splits;
+    split = b % row_splits;
+  }
 }
 
 // MFMA helper: D = A * B + C on one 32x32x16 bf16 step.  PASS 1 puts the keys on the A side
@@ -172,22 +191,25 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
   const uint32_t halves1 = (desc >> 16) & 3u;              // halves of every tile that slot 1 computes
 
   // ---- this workgroup's share of the tile sequence, one segment (part of one problem) at a time
-  const int x_begin = (int)((int64_t)blockIdx.x * a.total_tiles / gridDim.x);
-  const int x_end = (int)((int64_t)(blockIdx.x + 1) * a.total_tiles / gridDim.x);
-  // the request the walk stands in: request cur_seq of problem cur_hi, whose lead begins at position cur_acc
-  int cur_hi = x_begin / a.tiles_per_problem, cur_seq = 0, cur_acc = 0;
+  int team, split;
+  team_of((int)blockIdx.x, (int)gridDim.x, a.row_splits, team, split);
+  team = __builtin_amdgcn_readfirstlane(team);
+  split = __builtin_amdgcn_readfirstlane(split);
+  const int teams = (int)gridDim.x / a.row_splits;
+  const int x_begin = (int)((int64_t)team * a.total_tiles / teams);
+  const int x_end = (int)((int64_t)(team + 1) * a.total_tiles / teams);
+  // the request the walk stands in: request cur_seq of problem cur_lz, whose lead begins at position cur_acc
+  int cur_lz = x_begin / a.tiles_per_problem, cur_seq = 0, cur_acc = 0;
   if (a.n_seqs > 16 && x_begin < x_end)                      // few requests: walking there from the first one is as quick
-    locate_first<NT>(a.cu_seqlens, a.n_seqs, a.lead, a.key_trim, x_begin - cur_hi * a.tiles_per_problem, cur_seq, cur_acc);
+    locate_first<NT>(a.cu_seqlens, a.n_seqs, a.lead, a.key_trim, x_begin - cur_lz * a.tiles_per_problem, cur_seq, cur_acc);
   cur_seq = __builtin_amdgcn_readfirstlane(cur_seq);         // the same in every lane: scalar registers from here on
   cur_acc = __builtin_amdgcn_readfirstlane(cur_acc);
   for (int x = x_begin; x < x_end;) {
-  const int hi = x / a.tiles_per_problem;                  // (layer * Hkv + head) * row_splits + split
-  const int lz = hi / a.row_splits;
-  const int split = hi - lz * a.row_splits;
+  const int lz = x / a.tiles_per_problem;                  // layer * Hkv + head
   const int layer = lz / a.Hkv;
   const int head = lz - layer * a.Hkv;
-  if (hi != cur_hi) { cur_hi = hi; cur_seq = 0; cur_acc = 0; }     // crossed into the next problem: its first request
-  const int xr = x - hi * a.tiles_per_problem;
+  if (lz != cur_lz) { cur_lz = lz; cur_seq = 0; cur_acc = 0; }     // crossed into the next problem: its first request
+  const int xr = x - lz * a.tiles_per_problem;
   int tok0 = a.cu_seqlens[cur_seq], tok1 = a.cu_seqlens[cur_seq + 1];
   int tiles_of_seq = tiles_of(tok1 - tok0, a.key_trim);
   while (xr >= cur_acc + a.lead + tiles_of_seq && cur_seq < a.n_seqs - 1) {       // usually no step or one
@@ -589,7 +611,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     reduce_cols(ntiles - 1);
   } else {
     // merge the two half-wave views of each row, then one (max*c, sum) pair per slot row and segment
-    float* st = a.stats + ((int64_t)(blockIdx.x + hi * a.n_seqs + seq) * a.srows) * 2;
+    float* st = a.stats + ((int64_t)((team + lz * a.n_seqs + seq) * a.row_splits + split) * a.srows) * 2;
 #pragma unroll
     for (int sl = 0; sl < 2; ++sl) {
       const float m_r = sl == 0 ? m_run0 : m_run1, l_r = sl == 0 ? l_run0 : l_run1;
@@ -634,15 +656,15 @@ int resident_workgroups(Kernel kernel, int threads, std::atomic<int>* cache) {
   return cus * per_cu;
 }
 
-// One launch "wave": as many workgroups as the device holds at once, each with an equal share of the
-// tiles (at least kMinTilesPerWorkgroup, so that small problems are not all prologue), unless the caller
-// fixed the number (codecomp_params.score_workgroups).
-inline int score_grid(const Plan& pl, int resident) {
-  int g = resident > 0 ? resident : 256;
-  if (pl.grid_override > 0) g = pl.grid_override;
+// Teams of one launch "wave": as many workgroups as the device holds at once (row_splits of them per team), each
+// team with an equal share of the tiles (at least kMinTilesPerWorkgroup, so that small problems are not all
+// prologue), unless the caller fixed the number of workgroups (codecomp_params.score_workgroups).
+inline int score_teams(const Plan& pl, int resident) {
+  int g = (resident > 0 ? resident : 256) / pl.row_splits;
+  if (pl.grid_override > 0) g = pl.grid_override / pl.row_splits;
   else g = g < pl.real_tiles / kMinTilesPerWorkgroup ? g : pl.real_tiles / kMinTilesPerWorkgroup;
   if (g > pl.real_tiles) g = pl.real_tiles;
-  if (g > kMaxScoreGrid) g = kMaxScoreGrid;
+  if (g > kMaxScoreGrid / pl.row_splits) g = kMaxScoreGrid / pl.row_splits;
   return g < 1 ? 1 : g;
 }
 
@@ -650,10 +672,10 @@ template <int D, int NW, bool K8>
 int launch_passes(const Plan& pl, ScoreArgs a, hipStream_t stream, unsigned stages) {
   static std::atomic<int> cache1[kMaxDevices], cache2[kMaxDevices], cache2m[kMaxDevices];   // zero-initialised
   const dim3 block(NW * 64);
-  a.stat_wgs = score_grid(pl, resident_workgroups(score_pass_kernel<D, NW, 1, false, K8>, NW * 64, cache1));
+  a.stat_teams = score_teams(pl, resident_workgroups(score_pass_kernel<D, NW, 1, false, K8>, NW * 64, cache1));
   const bool any_tile = pl.real_tiles > 0;      // false: prefix-only softmax with no prefix anywhere
   if ((stages & CODECOMP_STAGE_ROW_STATS) && any_tile) {
-    score_pass_kernel<D, NW, 1, false, K8><<<dim3(a.stat_wgs), block, 0, stream>>>(a);
+    score_pass_kernel<D, NW, 1, false, K8><<<dim3(a.stat_teams * pl.row_splits), block, 0, stream>>>(a);
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
   if (stages & CODECOMP_STAGE_ROW_MERGE) {
@@ -661,11 +683,11 @@ int launch_passes(const Plan& pl, ScoreArgs a, hipStream_t stream, unsigned stag
   }
   if ((stages & CODECOMP_STAGE_MASS) && any_tile) {
     if (pl.variant & CODECOMP_VARIANT_GROUP_MAX) {
-      const int g = score_grid(pl, resident_workgroups(score_pass_kernel<D, NW, 2, true, K8>, NW * 64, cache2m));
-      score_pass_kernel<D, NW, 2, true, K8><<<dim3(g), block, 0, stream>>>(a);
+      const int g = score_teams(pl, resident_workgroups(score_pass_kernel<D, NW, 2, true, K8>, NW * 64, cache2m));
+      score_pass_kernel<D, NW, 2, true, K8><<<dim3(g * pl.row_splits), block, 0, stream>>>(a);
     } else {
-      const int g = score_grid(pl, resident_workgroups(score_pass_kernel<D, NW, 2, false, K8>, NW * 64, cache2));
-      score_pass_kernel<D, NW, 2, false, K8><<<dim3(g), block, 0, stream>>>(a);
+      const int g = score_teams(pl, resident_workgroups(score_pass_kernel<D, NW, 2, false, K8>, NW * 64, cache2));
+      score_pass_kernel<D, NW, 2, false, K8><<<dim3(g * pl.row_splits), block, 0, stream>>>(a);
     }
     if (hipError_t e = hipGetLastError()) return (int)e;
   }
