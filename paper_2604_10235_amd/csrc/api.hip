@@ -161,6 +161,23 @@ int make_plan(const codecomp_params* p, Plan* pl) {
   pl->off_uraw = off;  off = align256(off + (size_t)pl->row_splits * LH * pl->T * sizeof(float));
   pl->off_member = off; off = align256(off + (size_t)pl->T);
   pl->off_member_count = off; off = align256(off + (size_t)pl->n_seqs * sizeof(int32_t));
+  // selection by parts: per (layer*head, part) the first-digit counts and the number of candidates admitted whatever
+  // the cut; per (layer*head, request) what the parts agreed on.  The keys near the cut reuse the raw attention mass
+  // (dead once the scores exist): one 32-bit word per token and layer*head, exactly its size.
+  pl->sel_parts = 0;
+  const int max_npre = max_n - p->window;
+  if (max_npre > kSelectMaxCandidates || (max_npre >= kPartMinCandidates && LH * (size_t)p->n_seqs < (size_t)kPartFewProblems)) {
+    int64_t parts = 0;
+    for (int r = 0; r < p->n_seqs; ++r) {
+      const int npre = p->cu_seqlens_host[r + 1] - p->cu_seqlens_host[r] - p->window;
+      parts += npre > kPartChunk ? (npre + kPartChunk - 1) / kPartChunk : 1;
+    }
+    if (parts > (1 << 24)) return CODECOMP_EINVAL_SHAPE;
+    pl->sel_parts = (int)parts;
+    pl->off_part_hist = off; off = align256(off + LH * (size_t)parts * kFirstDigitBins * sizeof(uint16_t));
+    pl->off_part_sure = off; off = align256(off + LH * (size_t)parts * sizeof(int32_t));
+    pl->off_part_head = off; off = align256(off + LH * (size_t)pl->n_seqs * 8 * sizeof(uint32_t));
+  }
   pl->ws_bytes = off;
   return CODECOMP_OK;
 }
@@ -230,7 +247,7 @@ int codecomp_select(const float* scores, const codecomp_params* params, int32_t*
   if (int rc = make_plan(params, &pl)) return rc;
   if (pl.select_mode != CODECOMP_SELECT_ADDITIVE) return CODECOMP_EINVAL_MODE;   // the prior is needed: other entry
   if (int rc = check_ws(pl, workspace, workspace_bytes)) return rc;
-  return launch_select(pl, scores, idx, (hipStream_t)hip_stream);
+  return launch_select(pl, scores, idx, workspace, (hipStream_t)hip_stream);
 }
 
 int codecomp_select_two_stage(const float* scores, const float* prior, const codecomp_params* params, int32_t* idx,
@@ -266,7 +283,7 @@ int codecomp_compress(const void* q_obs, const void* k, const void* v, const flo
   if (pl.select_mode == CODECOMP_SELECT_TWO_STAGE) {
     if (int rc = launch_select_two_stage(pl, scores, prior, idx, workspace, s)) return rc;
   } else {
-    if (int rc = launch_select(pl, scores, idx, s)) return rc;
+    if (int rc = launch_select(pl, scores, idx, workspace, s)) return rc;
   }
   return launch_gather(pl, k, v, idx, k_out, v_out, s);
 }

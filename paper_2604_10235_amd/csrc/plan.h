@@ -14,7 +14,16 @@ constexpr int kTileKeys = 64;         // keys staged through LDS per pipeline st
 constexpr int kMaxScoreGrid = 2048;   // most workgroups a score pass is launched with
 constexpr int kMinTilesPerWorkgroup = 4;
 constexpr int kLeadTiles = 4;         // a segment start (query fragments, first K tile) costs about this many tiles
-constexpr int kSelectThreads = 1024;  // one workgroup per (layer, head, request) in select
+constexpr int kSelectThreads = 1024;  // one workgroup per (layer, head, request) in select, for short requests
+// Longer requests are selected by several workgroups each: parts of kPartChunk candidates, one 256-thread workgroup
+// per part and step (three steps: first-digit counts, the candidates near the cut, the ordered output).
+constexpr int kPartThreads = 256;
+constexpr int kPartItems = 32;                             // candidates a thread holds
+constexpr int kPartChunk = kPartThreads * kPartItems;      // candidates per part
+constexpr int kSelectMaxCandidates = 65536;                // most candidates one workgroup keeps in registers (64 per thread)
+constexpr int kPartMinCandidates = 16384;                  // few problems: parts are used from this many candidates on
+constexpr int kPartFewProblems = 100;                      // (layer, head, request) problems below which one workgroup each leaves the device idle
+constexpr int kFirstDigitBins = 2048;
 
 struct Plan {
   int L, Hq, Hkv, G, d, W, pool, n_seqs;
@@ -47,6 +56,9 @@ struct Plan {
   const int32_t* cu_budgets_dev;
   // workspace layout (byte offsets, each 256-byte aligned)
   size_t off_stats, off_lse, off_uraw, off_member, off_member_count, ws_bytes;
+  // selection by parts (0 parts: one workgroup per request does it all)
+  int sel_parts;             // sum over requests of max(1, ceil((N_r - W) / kPartChunk))
+  size_t off_part_hist, off_part_sure, off_part_head;
 };
 
 // Spreads `row_blocks` blocks over the waves of a workgroup (fills waves, wave_desc, rb_holder).
@@ -57,7 +69,7 @@ int make_plan(const codecomp_params* p, Plan* plan);
 
 int launch_score(const Plan& pl, const void* q, const void* k, const float* prior, float* scores,
                  void* workspace, hipStream_t stream, unsigned stages = CODECOMP_STAGE_ALL);
-int launch_select(const Plan& pl, const float* scores, int32_t* idx, hipStream_t stream);
+int launch_select(const Plan& pl, const float* scores, int32_t* idx, void* workspace, hipStream_t stream);
 int launch_select_two_stage(const Plan& pl, const float* scores, const float* prior, int32_t* idx, void* workspace,
                             hipStream_t stream);
 int launch_gather(const Plan& pl, const void* k, const void* v, const int32_t* idx, void* k_out, void* v_out,

@@ -2,13 +2,26 @@
 // of the prefix [0, N - W); equal scores go to the lower index; indices come out ascending
 // (section "Attention-based KV Cache Compression": the best-scored context tokens are kept until the budget is used up).
 //
-// One workgroup of 1024 threads owns one problem.  An MSB-first radix select over order-preserving
-// integer images of the float scores (digits of 11, 11 and 10 bits, LDS histogram) finds the score
-// of the last admitted token and how many tokens tied at that score are admitted; one ordered pass
-// (workgroup prefix sums of "sure" and "tied" flags) then writes the indices already sorted.
-// The candidates are read from memory ONCE, all loads in flight together, and stay in registers
-// through the three digit passes and the ordered pass (up to 64 per thread, N - W <= 65536); longer
-// requests fall back to re-reading the score row, which then lives in L2.
+// An MSB-first radix select over order-preserving integer images of the float scores (digits of 11, 11
+// and 10 bits, LDS histograms) finds the score of the last admitted token and how many tokens tied at
+// that score are admitted; one ordered pass (prefix sums of "sure" and "tied" flags) then writes the
+// indices already sorted.  No float is ever added, nothing depends on the order in which workgroups run:
+// the result is the same bits on every call.
+//
+// Requests of at most 65536 candidates in a batch with enough problems to occupy the device: one workgroup of 1024 threads owns one
+// (layer, head, request) problem; the candidates are read from memory once, all loads in flight together,
+// and stay in registers through the three digit passes and the ordered pass.
+// A batch with a longer request, or with few problems and long requests: every request is cut into parts of 8192 candidates and four kernels run
+// one 256-thread workgroup per part (the third one per request), so that a problem is spread over as many compute units as it has parts
+// and a ragged batch is not paced by its longest request:
+//   counts  every part counts the first digit of its candidates (2048 bins) and stores the counts;
+//   near    every part adds up the counts of its request, finds the bin that holds the cut, and appends its
+//           candidates of that bin (keys only, in token order) to the request's list, at the place the
+//           counts of the earlier parts give it; it also stores how many of its candidates lie above that bin;
+//   resolve one workgroup per request finishes the radix select on the list (two more digits; the list is short
+//           unless the scores crowd into one bin);
+//   emit    every part counts what the earlier parts contribute and writes its own admitted indices at their
+//           final places.
 //
 // Two selection rules share these pieces:
 //   additive   : one selection on c = pooled attention + lambda * prior (the score kernel's output);
@@ -30,6 +43,7 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 }
 
 constexpr int kSelTileItems = 4;    // consecutive candidates per thread inside one ordered tile
+constexpr int kSelMaxItems = kSelectMaxCandidates / kSelectThreads;   // most candidates a thread of the one-workgroup kernels holds
 constexpr int kSelTile = kSelectThreads * kSelTileItems;
 
 constexpr int kHistCopies = 8;      // private copies of the first-digit histogram, picked by lane % 8
@@ -42,7 +56,7 @@ struct SelectShared {
   int tile_sure, tile_tie;
   // class (0 out, 1 tied at the cut, 2 in) of every register-resident candidate, one byte each, indexed by
   // candidate: written in the load layout, read back as runs of consecutive candidates per thread
-  unsigned int cls_words[kSelectThreads * 64 / 4];
+  unsigned int cls_words[kSelectThreads * kSelMaxItems / 4];
 };
 
 // One candidate into the digit histogram.  CROWDED (the first digit: every candidate takes part and the scores
@@ -153,34 +167,30 @@ __device__ __forceinline__ void tile_scan(SelectShared& sh, int nsure, int ntie,
 //   key(j)      order-preserving integer image of its score,
 //   eligible(j) whether it competes in the radix select,
 //   forced(j)   whether it is admitted regardless (stage 2: members of the protected set).
-// ITEMS > 0: candidates are loaded once into registers (npre <= kSelectThreads * ITEMS);
-// ITEMS == 0: every pass re-reads them.
+// The candidates are loaded once into registers, ITEMS per thread (npre <= kSelectThreads * ITEMS).
 // emit(j, admitted, pos) is called for every j, pos = number of admitted candidates before j.
 template <int ITEMS, class Source, class Emit>
 __device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emit, int npre, int need) {
-  constexpr int NT = kSelectThreads;
   const int tid = threadIdx.x;
-  constexpr int NREG = ITEMS > 0 ? ITEMS : 1;
-  uint32_t keys[NREG];
+  static_assert(ITEMS > 0 && ITEMS % kSelTileItems == 0 && ITEMS <= kSelMaxItems, "register-resident candidates");
+  uint32_t keys[ITEMS];
   unsigned long long elig = 0, forc = 0;       // one bit per register slot
   // slot s of this thread holds candidate j = (s / 4) * kSelTile + tid * 4 + (s % 4): tiles in order, 4 consecutive
-  if constexpr (ITEMS > 0) {
-    if (npre > 0) {                            // the same for every thread
-      // unconditional loads (index clamped into the row) so that all of them are in flight together
+  if (npre > 0) {                              // the same for every thread
+    // unconditional loads (index clamped into the row) so that all of them are in flight together
 #pragma unroll
-      for (int s = 0; s < ITEMS; ++s) {
-        const int j = (s / kSelTileItems) * kSelTile + tid * kSelTileItems + (s % kSelTileItems);
-        const int jc = j < npre ? j : npre - 1;
-        const uint32_t key = src.key(jc);
-        const bool el = src.eligible(jc), fo = src.forced(jc);
-        keys[s] = j < npre ? key : 0u;
-        if (j < npre && el) elig |= 1ull << s;
-        if (j < npre && fo) forc |= 1ull << s;
-      }
-    } else {
-#pragma unroll
-      for (int s = 0; s < ITEMS; ++s) keys[s] = 0u;
+    for (int s = 0; s < ITEMS; ++s) {
+      const int j = (s / kSelTileItems) * kSelTile + tid * kSelTileItems + (s % kSelTileItems);
+      const int jc = j < npre ? j : npre - 1;
+      const uint32_t key = src.key(jc);
+      const bool el = src.eligible(jc), fo = src.forced(jc);
+      keys[s] = j < npre ? key : 0u;
+      if (j < npre && el) elig |= 1ull << s;
+      if (j < npre && fo) forc |= 1ull << s;
     }
+  } else {
+#pragma unroll
+    for (int s = 0; s < ITEMS; ++s) keys[s] = 0u;
   }
 
   uint32_t tau = 0xFFFFFFFFu;
@@ -193,30 +203,11 @@ __device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emi
       const uint32_t himask = pass_himask(pass);
       const int copies = pass == 0 ? kHistCopies : 1;
       hist_clear(sh, nbins, copies);
-      if constexpr (ITEMS > 0) {
 #pragma unroll
-        for (int s = 0; s < ITEMS; ++s) {
-          const bool match = ((elig >> s) & 1ull) && (keys[s] & himask) == prefix;
-          if (pass == 0) hist_add<true>(sh, match, (keys[s] >> shift) & (uint32_t)(nbins - 1));
-          else hist_add<false>(sh, match, (keys[s] >> shift) & (uint32_t)(nbins - 1));
-        }
-      } else {
-        const int npad = (npre + NT - 1) / NT * NT;   // uniform trip counts: every lane takes part in the ballots
-        constexpr int UNR = 8;                        // loads in flight per thread
-        for (int j0 = tid; j0 < npad; j0 += NT * UNR) {
-          uint32_t k8[UNR];
-          bool v8[UNR];
-#pragma unroll
-          for (int u = 0; u < UNR; ++u) {
-            const int j = j0 + u * NT;
-            k8[u] = 0u; v8[u] = false;
-            if (j < npre) { k8[u] = src.key(j); v8[u] = src.eligible(j); }
-          }
-#pragma unroll
-          for (int u = 0; u < UNR; ++u)
-            if (pass == 0) hist_add<true>(sh, v8[u] && (k8[u] & himask) == prefix, (k8[u] >> shift) & (uint32_t)(nbins - 1));
-            else hist_add<false>(sh, v8[u] && (k8[u] & himask) == prefix, (k8[u] >> shift) & (uint32_t)(nbins - 1));
-        }
+      for (int s = 0; s < ITEMS; ++s) {
+        const bool match = ((elig >> s) & 1ull) && (keys[s] & himask) == prefix;
+        if (pass == 0) hist_add<true>(sh, match, (keys[s] >> shift) & (uint32_t)(nbins - 1));
+        else hist_add<false>(sh, match, (keys[s] >> shift) & (uint32_t)(nbins - 1));
       }
       hist_pick(sh, nbins, copies, shift, prefix, remaining);
     }
@@ -224,83 +215,47 @@ __device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emi
     ties = (int)remaining;
   }
 
-  // ---- ordered pass
-  int carry_sure = 0, carry_tie = 0;
-  const int ntiles = (npre + kSelTile - 1) / kSelTile;
-  auto do_tile = [&](int t, const int (&cls)[kSelTileItems]) __attribute__((always_inline)) {
-    int nsure = 0, ntie = 0;
+  // ---- ordered pass.  The classes (0 out, 1 tied at the cut, 2 in) go through LDS so that every thread ends up
+  // with ITEMS consecutive candidates: one workgroup prefix sum, and each thread writes its admitted indices to
+  // consecutive places.
+  constexpr int T4 = ITEMS / kSelTileItems;
 #pragma unroll
-    for (int e = 0; e < kSelTileItems; ++e) { nsure += cls[e] == 2; ntie += cls[e] == 1; }
-    int bs, bt, ts, tt;
-    tile_scan(sh, nsure, ntie, bs, bt, ts, tt);
-    int ps = carry_sure + bs, pt = carry_tie + bt;
+  for (int t = 0; t < T4; ++t) {
+    unsigned int word = 0;
 #pragma unroll
     for (int e = 0; e < kSelTileItems; ++e) {
-      const int j = t * kSelTile + tid * kSelTileItems + e;
+      const int s = t * kSelTileItems + e;
+      const bool el = (elig >> s) & 1ull, fo = (forc >> s) & 1ull;
+      const unsigned int c = fo ? 2u : (el ? (keys[s] > tau ? 2u : (keys[s] == tau ? 1u : 0u)) : 0u);
+      word |= c << (8 * e);
+    }
+    sh.cls_words[t * kSelectThreads + tid] = word;       // candidates 4 * (t * 1024 + tid) .. + 3
+  }
+  __syncthreads();
+  unsigned int mine[T4];
+  int nsure = 0, ntie = 0;
+#pragma unroll
+  for (int t = 0; t < T4; ++t) {
+    mine[t] = sh.cls_words[tid * T4 + t];                // candidates tid * ITEMS + 4 t .. + 3
+#pragma unroll
+    for (int e = 0; e < kSelTileItems; ++e) {
+      const unsigned int c = (mine[t] >> (8 * e)) & 255u;
+      nsure += c == 2u; ntie += c == 1u;
+    }
+  }
+  int ps, pt, ts, tt;
+  tile_scan(sh, nsure, ntie, ps, pt, ts, tt);
+#pragma unroll
+  for (int t = 0; t < T4; ++t) {
+#pragma unroll
+    for (int e = 0; e < kSelTileItems; ++e) {
+      const int j = tid * ITEMS + t * kSelTileItems + e;
+      const unsigned int c = (mine[t] >> (8 * e)) & 255u;
       if (j < npre) {
-        const bool admitted = cls[e] == 2 || (cls[e] == 1 && pt < ties);
+        const bool admitted = c == 2u || (c == 1u && pt < ties);
         emit(j, admitted, ps + min(pt, ties));
       }
-      ps += cls[e] == 2; pt += cls[e] == 1;
-    }
-    carry_sure += ts; carry_tie += tt;
-  };
-  if constexpr (ITEMS > 0) {
-    // The classes go through LDS so that every thread ends up with ITEMS consecutive candidates: one workgroup
-    // prefix sum instead of one per tile, and each thread writes its admitted indices to consecutive places.
-    constexpr int T4 = ITEMS / kSelTileItems;
-#pragma unroll
-    for (int t = 0; t < T4; ++t) {
-      unsigned int word = 0;
-#pragma unroll
-      for (int e = 0; e < kSelTileItems; ++e) {
-        const int s = t * kSelTileItems + e;
-        const bool el = (elig >> s) & 1ull, fo = (forc >> s) & 1ull;
-        const unsigned int c = fo ? 2u : (el ? (keys[s] > tau ? 2u : (keys[s] == tau ? 1u : 0u)) : 0u);
-        word |= c << (8 * e);
-      }
-      sh.cls_words[t * kSelectThreads + tid] = word;       // candidates 4 * (t * 1024 + tid) .. + 3
-    }
-    __syncthreads();
-    unsigned int mine[T4];
-    int nsure = 0, ntie = 0;
-#pragma unroll
-    for (int t = 0; t < T4; ++t) {
-      mine[t] = sh.cls_words[tid * T4 + t];                // candidates tid * ITEMS + 4 t .. + 3
-#pragma unroll
-      for (int e = 0; e < kSelTileItems; ++e) {
-        const unsigned int c = (mine[t] >> (8 * e)) & 255u;
-        nsure += c == 2u; ntie += c == 1u;
-      }
-    }
-    int ps, pt, ts, tt;
-    tile_scan(sh, nsure, ntie, ps, pt, ts, tt);
-#pragma unroll
-    for (int t = 0; t < T4; ++t) {
-#pragma unroll
-      for (int e = 0; e < kSelTileItems; ++e) {
-        const int j = tid * ITEMS + t * kSelTileItems + e;
-        const unsigned int c = (mine[t] >> (8 * e)) & 255u;
-        if (j < npre) {
-          const bool admitted = c == 2u || (c == 1u && pt < ties);
-          emit(j, admitted, ps + min(pt, ties));
-        }
-        ps += c == 2u; pt += c == 1u;
-      }
-    }
-  } else {
-    for (int t = 0; t < ntiles; ++t) {
-      int cls[kSelTileItems];
-#pragma unroll
-      for (int e = 0; e < kSelTileItems; ++e) {
-        const int j = t * kSelTile + tid * kSelTileItems + e;
-        cls[e] = 0;
-        if (j < npre) {
-          if (src.forced(j)) cls[e] = 2;
-          else if (src.eligible(j)) { const uint32_t key = src.key(j); cls[e] = key > tau ? 2 : (key == tau ? 1 : 0); }
-        }
-      }
-      do_tile(t, cls);
+      ps += c == 2u; pt += c == 1u;
     }
   }
 }
@@ -361,7 +316,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
     for (int j = tid; j < npre; j += NT) out[j] = j;
     return;
   }
-  if (ITEMS > 0 && npre > NT * ITEMS) return;   // the host picks ITEMS from the longest request: cannot happen
+  if (npre > NT * ITEMS) return;         // the host picks ITEMS from the longest request: cannot happen
   ScoreSource src = {a.scores + (int64_t)lz * a.T + s0};
   select_wg<ITEMS>(sh, src, [&](int j, bool admitted, int pos) { if (admitted) out[pos] = j; }, npre, need);
 }
@@ -397,7 +352,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_stage1_kernel(SelectArg
   bspan = min(bp, bspan);
   const int need = min(bspan, flagged);
   if (tid == 0) a.member_count[seq] = need;
-  if (need <= 0 || (ITEMS > 0 && npre > NT * ITEMS)) {
+  if (need <= 0 || npre > NT * ITEMS) {
     for (int j = tid; j < npre; j += NT) member[j] = 0;
     return;
   }
@@ -428,17 +383,491 @@ __global__ __launch_bounds__(kSelectThreads) void select_stage2_kernel(SelectArg
     for (int j = tid; j < npre; j += NT) out[j] = j;
     return;
   }
-  if (ITEMS > 0 && npre > NT * ITEMS) return;
+  if (npre > NT * ITEMS) return;
   FillSource src = {a.scores + (int64_t)lz * a.T + s0, a.member + s0};
   select_wg<ITEMS>(sh, src, [&](int j, bool admitted, int pos) { if (admitted) out[pos] = j; }, npre, need);
 }
 
-// candidates kept in registers per thread, chosen from the longest request
+// ---------------------------------------------------------------------------------------------------------
+// Selection by parts: several workgroups per problem, three kernels (see the head of this file).
+// ---------------------------------------------------------------------------------------------------------
+
+struct PartArgs {
+  uint16_t* hist;        // [lz][part][2048] first-digit counts of each part (at most kPartChunk each)
+  int32_t* sure;         // [lz][part] candidates of the part admitted whatever the cut: bins above the cut's, forced ones
+  uint32_t* head;        // [lz][request][8]: mode, first digit of the cut, rank of the cut inside that bin, size of that bin,
+                         //                   number of competing candidates admitted
+  uint32_t* list;        // [lz][T] keys of the candidates in the cut's bin, per request from its first token on, in token order
+  int parts;             // parts of all requests together
+};
+
+enum { kModeNone = 0, kModeAll = 1, kModeSelect = 2 };   // no competing candidate admitted / all of them / a real selection
+
+constexpr int kPartCopies = 4;       // private copies of a histogram (lane % 4)
+constexpr int kPartHistWords = 8 * (kFirstDigitBins / 2 + 1);   // 8 packed copies of the first-digit counts, or 4 plain copies of a digit
+static_assert(kPartHistWords >= kPartCopies * kHistStride, "histogram storage of the part kernels");
+
+struct PartShared {
+  unsigned int hist[kPartHistWords];
+  unsigned int prefix, need;
+  int red[4][kPartThreads / 64];
+  int found[4];
+};
+
+// The three rules as seen by the part kernels: where the candidates come from, how many of them are admitted, what
+// is written for a candidate and for the window.
+struct RuleAdditive {
+  using Src = ScoreSource;
+  __device__ static Src source(const SelectArgs& a, int lz, int s0) { return {a.scores + (int64_t)lz * a.T + s0}; }
+  __device__ static int need(const SelectArgs& a, int, int budget, int npre, int, int& mode) {
+    const int need = budget - a.W;
+    mode = need <= 0 ? kModeNone : (need >= npre ? kModeAll : kModeSelect);
+    return need;
+  }
+  __device__ static void emit(const SelectArgs& a, int lz, int, int o0, int j, bool admitted, int pos, int limit) {
+    if (admitted && (unsigned)pos < (unsigned)limit) a.idx[(int64_t)lz * a.TB + o0 + pos] = j;   // pos < limit always: belt and braces
+  }
+  __device__ static void window(const SelectArgs& a, int lz, int, int, int o0, int budget, int npre, int, int t) {
+    a.idx[(int64_t)lz * a.TB + o0 + (budget - a.W) + t] = npre + t;
+  }
+};
+struct RuleStage1 {     // once per request: which marked tokens the span budget keeps
+  using Src = PriorSource;
+  __device__ static Src source(const SelectArgs& a, int, int s0) { return {a.prior + s0}; }
+  __device__ static int need(const SelectArgs& a, int, int budget, int, int marked, int& mode) {
+    const int bp = budget - a.W;
+    int bspan = max(a.span_min, (int)floor((double)a.span_ratio * (double)bp));
+    bspan = min(bp, bspan);
+    const int need = min(bspan, marked);
+    mode = need <= 0 ? kModeNone : kModeSelect;       // need == marked: the selection admits every marked token
+    return need;
+  }
+  __device__ static void emit(const SelectArgs& a, int, int s0, int, int j, bool admitted, int, int) {
+    a.member[s0 + j] = admitted ? 1 : 0;
+  }
+  __device__ static void window(const SelectArgs& a, int, int seq, int s0, int, int, int npre, int need, int t) {
+    a.member[s0 + npre + t] = 0;
+    if (t == 0) a.member_count[seq] = need > 0 ? need : 0;
+  }
+};
+struct RuleStage2 {     // per (layer, head, request): attention fills what stage 1 left
+  using Src = FillSource;
+  __device__ static Src source(const SelectArgs& a, int lz, int s0) { return {a.scores + (int64_t)lz * a.T + s0, a.member + s0}; }
+  __device__ static int need(const SelectArgs& a, int seq, int budget, int npre, int, int& mode) {
+    const int bp = budget - a.W;
+    if (bp <= 0) { mode = kModeNone; return 0; }
+    if (bp >= npre) { mode = kModeAll; return bp; }
+    const int need = bp - a.member_count[seq];
+    mode = need > 0 ? kModeSelect : kModeNone;
+    return need;
+  }
+  __device__ static void emit(const SelectArgs& a, int lz, int, int o0, int j, bool admitted, int pos, int limit) {
+    if (admitted && (unsigned)pos < (unsigned)limit) a.idx[(int64_t)lz * a.TB + o0 + pos] = j;   // pos < limit always: belt and braces
+  }
+  __device__ static void window(const SelectArgs& a, int lz, int, int, int o0, int budget, int npre, int, int t) {
+    a.idx[(int64_t)lz * a.TB + o0 + (budget - a.W) + t] = npre + t;
+  }
+};
+
+__device__ __forceinline__ int parts_of(int npre) { return npre > kPartChunk ? (npre + kPartChunk - 1) / kPartChunk : 1; }
+
+// Sum of one int over the workgroup (all threads call it; `slot` picks one of four scratch rows so that
+// back-to-back calls need no barrier in between).
+__device__ __forceinline__ int part_sum(PartShared& sh, int v, int slot) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  if ((threadIdx.x & 63) == 0) sh.red[slot][threadIdx.x >> 6] = v;
+  __syncthreads();
+  int t = 0;
+#pragma unroll
+  for (int w = 0; w < kPartThreads / 64; ++w) t += sh.red[slot][w];
+  return t;
+}
+
+// Exclusive prefix over the threads of the workgroup of two counts, and their totals (all threads call it).
+__device__ __forceinline__ void part_scan2(PartShared& sh, int a, int b, int& before_a, int& before_b, int& tot_a, int& tot_b) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int sa = a, sb = b;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int oa = __shfl_up(sa, off), ob = __shfl_up(sb, off);
+    if (lane >= off) { sa += oa; sb += ob; }
+  }
+  __syncthreads();                                 // the scratch rows may still be read from an earlier call
+  if (lane == 63) { sh.red[0][wave] = sa; sh.red[1][wave] = sb; }
+  __syncthreads();
+  before_a = sa - a; before_b = sb - b; tot_a = 0; tot_b = 0;
+#pragma unroll
+  for (int w = 0; w < kPartThreads / 64; ++w) {
+    if (w < wave) { before_a += sh.red[0][w]; before_b += sh.red[1][w]; }
+    tot_a += sh.red[0][w]; tot_b += sh.red[1][w];
+  }
+}
+
+// Which request and which of its parts workgroup `gp` of a launch works on; `first` = number of the request's first
+// part.  All threads call it (two barriers): every thread adds up the parts of a share of the requests, a prefix sum
+// over the threads finds the share that holds gp, its owner walks it.
+__device__ __forceinline__ void locate_part(PartShared& sh, const int32_t* cu, int n_seqs, int W, int gp, int& seq, int& part, int& first) {
+  const int tid = threadIdx.x;
+  const int per = (n_seqs + kPartThreads - 1) / kPartThreads;
+  const int r0 = min(tid * per, n_seqs), r1 = min(r0 + per, n_seqs);
+  int mine = 0;
+  for (int r = r0; r < r1; ++r) mine += parts_of(cu[r + 1] - cu[r] - W);
+  int before, dummy_b, total, dummy_t;
+  part_scan2(sh, mine, 0, before, dummy_b, total, dummy_t);
+  if (tid == 0) { sh.found[0] = n_seqs - 1; sh.found[1] = 0; }      // gp past the end never happens (grid = total parts)
+  __syncthreads();
+  if (gp >= before && gp < before + mine) {                         // exactly one thread
+    int pos = before, r = r0;
+    for (;; ++r) {
+      const int np = parts_of(cu[r + 1] - cu[r] - W);
+      if (gp < pos + np) break;
+      pos += np;
+    }
+    sh.found[0] = r; sh.found[1] = pos;
+  }
+  __syncthreads();
+  seq = sh.found[0]; first = sh.found[1]; part = gp - first;
+  __syncthreads();                                                  // found[] and the scratch rows are reused
+}
+
+// Candidate in slot s of this thread: the part is cut into tiles of 4 * kPartThreads candidates, a thread holds 4
+// consecutive candidates of every tile (the loads of a wave cover whole cache lines).
+constexpr int kPartTile = 4 * kPartThreads;
+constexpr int kPartTiles = kPartItems / 4;
+__device__ __forceinline__ int part_index(int part, int s) {
+  return part * kPartChunk + (s >> 2) * kPartTile + (int)threadIdx.x * 4 + (s & 3);
+}
+
+template <class Src>
+__device__ __forceinline__ void part_load(const Src& src, int npre, int part, uint32_t (&keys)[kPartItems], unsigned& elig, unsigned& forc) {
+  static_assert(kPartItems <= 32 && kPartItems % 4 == 0, "one flag bit per candidate, whole tiles");
+  elig = 0; forc = 0;
+  if (npre > 0) {
+#pragma unroll
+    for (int s = 0; s < kPartItems; ++s) {                          // unconditional, clamped: all loads in flight together
+      const int j = part_index(part, s), jc = j < npre ? j : npre - 1;
+      const uint32_t key = src.key(jc);
+      const bool el = src.eligible(jc), fo = src.forced(jc);
+      keys[s] = j < npre ? key : 0u;
+      if (j < npre && el) elig |= 1u << s;
+      if (j < npre && fo) forc |= 1u << s;
+    }
+  } else {
+#pragma unroll
+    for (int s = 0; s < kPartItems; ++s) keys[s] = 0u;
+  }
+}
+
+// Places in token order.  In: per tile, a count (or two counts below 2^16 packed into the halves of a word) over this
+// thread's 4 candidates of the tile.  Out: per tile, the same count(s) over all candidates of the part that come before
+// them.  All threads call it.  The counts go through LDS as a [tile][thread] table, which is token order when read flat.
+__device__ __forceinline__ void part_order(PartShared& sh, const unsigned int (&cnt)[kPartTiles], unsigned int (&before)[kPartTiles]) {
+  unsigned int* table = sh.hist;                         // free at this point in both callers
+  const int tid = threadIdx.x;
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < kPartTiles; ++t) table[t * kPartThreads + tid] = cnt[t];
+  __syncthreads();
+  unsigned int loc[kPartTiles], run = 0;
+#pragma unroll
+  for (int i = 0; i < kPartTiles; ++i) { loc[i] = run; run += table[tid * kPartTiles + i]; }
+  int ba, bb, ta, tb;
+  part_scan2(sh, (int)(run & 0xFFFFu), (int)(run >> 16), ba, bb, ta, tb);
+  const unsigned int base = (unsigned int)ba | ((unsigned int)bb << 16);
+#pragma unroll
+  for (int i = 0; i < kPartTiles; ++i) table[tid * kPartTiles + i] = base + loc[i];
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < kPartTiles; ++t) before[t] = table[t * kPartThreads + tid];
+  __syncthreads();
+}
+
+__device__ __forceinline__ void part_hist_clear(PartShared& sh, int nbins) {
+  for (int b = threadIdx.x; b < (kPartCopies - 1) * kHistStride + nbins; b += kPartThreads) sh.hist[b] = 0;
+  __syncthreads();
+}
+
+// counts: first digit of the part's competing candidates.  Every bin is stored, so nothing has to be cleared beforehand.
+template <class Rule>
+__global__ __launch_bounds__(kPartThreads) void part_counts_kernel(SelectArgs a, PartArgs c) {
+  __shared__ PartShared sh;
+  const int tid = threadIdx.x, gp = blockIdx.x, lz = blockIdx.y;
+  int seq, part, first;
+  locate_part(sh, a.cu_seqlens, a.n_seqs, a.W, gp, seq, part, first);
+  const int s0 = a.cu_seqlens[seq];
+  const int npre = a.cu_seqlens[seq + 1] - s0 - a.W;
+  uint32_t keys[kPartItems];
+  unsigned elig, forc;
+  part_load(Rule::source(a, lz, s0), npre, part, keys, elig, forc);
+  // A part holds at most kPartChunk < 2^16 candidates: two bins share a word, and there is room for 8 private copies
+  // (lane % 8) of the table, which matters because the scores crowd into a few dozen bins.
+  constexpr int COPIES = 8, STRIDE = kFirstDigitBins / 2 + 1;
+  static_assert(COPIES * STRIDE <= kPartHistWords && kPartChunk < 65536, "packed first-digit counts");
+  for (int b = tid; b < COPIES * STRIDE; b += kPartThreads) sh.hist[b] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < kPartItems; ++s) {
+    const uint32_t bin = keys[s] >> 21;
+    if ((elig >> s) & 1u) atomicAdd(&sh.hist[(tid & (COPIES - 1)) * STRIDE + (bin >> 1)], 1u << (16 * (bin & 1u)));
+  }
+  __syncthreads();
+  uint32_t* out = reinterpret_cast<uint32_t*>(c.hist + ((int64_t)lz * c.parts + gp) * kFirstDigitBins);
+  for (int w = tid; w < kFirstDigitBins / 2; w += kPartThreads) {       // a sum below 2^16 per half: no carry between them
+    unsigned int t = 0;
+#pragma unroll
+    for (int k = 0; k < COPIES; ++k) t += sh.hist[k * STRIDE + w];
+    out[w] = t;
+  }
+}
+
+// near: the bin that holds the cut, and the request's list of the candidates in that bin.
+template <class Rule>
+__global__ __launch_bounds__(kPartThreads) void part_near_kernel(SelectArgs a, PartArgs c) {
+  __shared__ PartShared sh;
+  const int tid = threadIdx.x, gp = blockIdx.x, lz = blockIdx.y;
+  int seq, part, first;
+  locate_part(sh, a.cu_seqlens, a.n_seqs, a.W, gp, seq, part, first);
+  const int s0 = a.cu_seqlens[seq];
+  const int npre = a.cu_seqlens[seq + 1] - s0 - a.W;
+  const int budget = a.cu_budgets[seq + 1] - a.cu_budgets[seq];
+  const int nparts = parts_of(npre);
+  uint32_t keys[kPartItems];
+  unsigned elig, forc;
+  part_load(Rule::source(a, lz, s0), npre, part, keys, elig, forc);
+
+  // counts of the 8 bins this thread owns (bins 8 * tid ...), over all parts of the request and in this part alone
+  constexpr int OWN = kFirstDigitBins / kPartThreads;
+  static_assert(OWN == 8, "one 16-byte load per part and thread");
+  unsigned int tot[OWN], own[OWN];
+#pragma unroll
+  for (int i = 0; i < OWN; ++i) { tot[i] = 0; own[i] = 0; }
+  const uint16_t* hp = c.hist + ((int64_t)lz * c.parts + first) * kFirstDigitBins + tid * OWN;
+  constexpr int BATCH = 8;                                // loads in flight
+  for (int q0 = 0; q0 < nparts; q0 += BATCH) {
+    uint4 v[BATCH];
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u)
+      v[u] = *reinterpret_cast<const uint4*>(hp + (int64_t)min(q0 + u, nparts - 1) * kFirstDigitBins);
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) {
+      if (q0 + u >= nparts) continue;
+      const unsigned int w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+      for (int i = 0; i < OWN; ++i) {
+        const unsigned int x = (w[i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
+        tot[i] += x;
+        if (q0 + u == part) own[i] = x;
+      }
+    }
+  }
+  int mine = 0;
+#pragma unroll
+  for (int i = 0; i < OWN; ++i) mine += (int)tot[i];
+  // candidates in the bins of higher threads (higher bins hold larger keys), and all competing candidates
+  int below, dummy_b, total, dummy_t;
+  part_scan2(sh, mine, 0, below, dummy_b, total, dummy_t);
+  const int above = total - below - mine;
+  int mode;
+  const int need = Rule::need(a, seq, budget, npre, total, mode);
+  if (tid == 0) { sh.found[0] = 0; sh.found[1] = 0; sh.found[2] = 0; }
+  __syncthreads();
+  if (mode == kModeSelect && above < need && need <= above + mine) {   // exactly one thread: the cut lies in one of its bins
+    int higher = above;
+    for (int i = OWN - 1; i >= 0; --i) {
+      if (need <= higher + (int)tot[i]) { sh.found[0] = tid * OWN + i; sh.found[1] = need - higher; sh.found[2] = (int)tot[i]; break; }
+      higher += (int)tot[i];
+    }
+  }
+  __syncthreads();
+  const int b0 = sh.found[0];
+  if (part == 0 && tid == 0) {
+    uint32_t* h = c.head + ((int64_t)lz * a.n_seqs + seq) * 8;
+    h[0] = (uint32_t)mode; h[1] = (uint32_t)b0; h[2] = (uint32_t)sh.found[1]; h[3] = (uint32_t)sh.found[2];
+    h[4] = (uint32_t)need;
+  }
+  // candidates of this part admitted whatever the cut: its bins above b0 (none when nothing is selected), forced ones
+  int sure = __popc(forc);
+  if (mode == kModeSelect) {
+#pragma unroll
+    for (int i = 0; i < OWN; ++i) sure += tid * OWN + i > b0 ? (int)own[i] : 0;
+  }
+  sure = part_sum(sh, sure, 2);
+  if (tid == 0) c.sure[(int64_t)lz * c.parts + gp] = sure;
+  if (mode != kModeSelect) return;                                     // the same for every thread
+  // where this part's share of the list begins: candidates of the earlier parts in bin b0
+  int off = 0;
+  for (int q = tid; q < part; q += kPartThreads) off += c.hist[((int64_t)lz * c.parts + first + q) * kFirstDigitBins + b0];
+  off = part_sum(sh, off, 3);
+  unsigned int cnt[kPartTiles], before[kPartTiles];
+#pragma unroll
+  for (int t = 0; t < kPartTiles; ++t) {
+    cnt[t] = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) cnt[t] += ((elig >> (4 * t + e)) & 1u) && (int)(keys[4 * t + e] >> 21) == b0;
+  }
+  part_order(sh, cnt, before);
+  uint32_t* list = c.list + (int64_t)lz * a.T + s0 + off;              // at most npre entries per request: inside its tokens
+#pragma unroll
+  for (int t = 0; t < kPartTiles; ++t) {
+    unsigned int pos = before[t];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (((elig >> (4 * t + e)) & 1u) && (int)(keys[4 * t + e] >> 21) == b0) list[pos++] = keys[4 * t + e];
+  }
+}
+
+// One more digit of the radix select over the request's list (all threads call it).  Entries whose bits above the
+// digit equal `prefix` take part; afterwards `prefix` has the digit filled in and `remaining` is the rank inside it.
+__device__ __forceinline__ void part_digit(PartShared& sh, const uint32_t* list, int m, int shift, int nbins, uint32_t himask,
+                                           uint32_t& prefix, uint32_t& remaining) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  part_hist_clear(sh, nbins);
+  constexpr int UNR = 8;                                  // loads in flight per thread
+  for (int i0 = tid; i0 < m; i0 += kPartThreads * UNR) {
+    uint32_t k[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) k[u] = list[min(i0 + u * kPartThreads, m - 1)];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      if (i0 + u * kPartThreads < m && (k[u] & himask) == prefix)
+        atomicAdd(&sh.hist[(tid & (kPartCopies - 1)) * kHistStride + ((k[u] >> shift) & (uint32_t)(nbins - 1))], 1u);
+  }
+  __syncthreads();
+  for (int b = tid; b < nbins; b += kPartThreads) {
+    unsigned int t = 0;
+#pragma unroll
+    for (int k = 0; k < kPartCopies; ++k) t += sh.hist[k * kHistStride + b];
+    sh.hist[b] = t;
+  }
+  __syncthreads();
+  if (wave == 0) {                       // lane owns bins [lane * per, lane * per + per); higher bins hold larger keys
+    const int per = nbins / 64;
+    unsigned int mine = 0;
+    for (int i = 0; i < per; ++i) mine += sh.hist[lane * per + i];
+    unsigned int run = mine;             // inclusive suffix sum over lanes
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const unsigned int o = __shfl_down(run, off);
+      if (lane + off < 64) run += o;
+    }
+    const unsigned int above = run - mine;
+    if (above < remaining && remaining <= above + mine) {        // exactly one lane
+      unsigned int higher = above;
+      for (int i = per - 1; i >= 0; --i) {
+        const unsigned int cbin = sh.hist[lane * per + i];
+        if (remaining <= higher + cbin) { sh.prefix = prefix | ((uint32_t)(lane * per + i) << shift); sh.need = remaining - higher; break; }
+        higher += cbin;
+      }
+    }
+  }
+  __syncthreads();
+  prefix = sh.prefix;
+  remaining = sh.need;
+  __syncthreads();
+}
+
+// resolve: one workgroup per problem finishes the radix select on the request's list (two more digits) and leaves
+// the key of the cut and the number of candidates tied at it that are admitted.
+__global__ __launch_bounds__(kPartThreads) void part_resolve_kernel(SelectArgs a, PartArgs c) {
+  __shared__ PartShared sh;
+  const int seq = blockIdx.x, lz = blockIdx.y;
+  uint32_t* h = c.head + ((int64_t)lz * a.n_seqs + seq) * 8;
+  if ((int)h[0] != kModeSelect) return;                      // the same for every thread
+  const uint32_t* list = c.list + (int64_t)lz * a.T + a.cu_seqlens[seq];
+  const int m = (int)h[3];
+  uint32_t prefix = h[1] << 21, remaining = h[2];
+  part_digit(sh, list, m, 10, 2048, 0xFFE00000u, prefix, remaining);
+  part_digit(sh, list, m, 0, 1024, 0xFFFFFC00u, prefix, remaining);
+  if (threadIdx.x == 0) { h[5] = prefix; h[6] = remaining; }
+}
+
+// emit: every part writes its admitted candidates at their final places.
+template <class Rule>
+__global__ __launch_bounds__(kPartThreads) void part_emit_kernel(SelectArgs a, PartArgs c) {
+  __shared__ PartShared sh;
+  const int tid = threadIdx.x, gp = blockIdx.x, lz = blockIdx.y;
+  int seq, part, first;
+  locate_part(sh, a.cu_seqlens, a.n_seqs, a.W, gp, seq, part, first);
+  const int s0 = a.cu_seqlens[seq];
+  const int npre = a.cu_seqlens[seq + 1] - s0 - a.W;
+  const int o0 = a.cu_budgets[seq];
+  const int budget = a.cu_budgets[seq + 1] - o0;
+  uint32_t keys[kPartItems];
+  unsigned elig, forc;
+  part_load(Rule::source(a, lz, s0), npre, part, keys, elig, forc);
+  const uint32_t* h = c.head + ((int64_t)lz * a.n_seqs + seq) * 8;
+  const int mode = (int)h[0], b0 = (int)h[1], need = (int)h[4];
+  if (part == 0)
+    for (int t = tid; t < a.W; t += kPartThreads) Rule::window(a, lz, seq, s0, o0, budget, npre, need, t);
+  if (mode == kModeAll) {                                    // every candidate is kept at its own place
+#pragma unroll
+    for (int s = 0; s < kPartItems; ++s) {
+      const int j = part_index(part, s);
+      if (j < npre) Rule::emit(a, lz, s0, o0, j, true, j, budget - a.W);
+    }
+    return;
+  }
+  uint32_t tau = 0xFFFFFFFFu;
+  int ties = 0, above_before = 0, ties_before = 0;
+  if (mode == kModeSelect) {
+    const uint32_t* list = c.list + (int64_t)lz * a.T + s0;
+    tau = h[5];
+    ties = (int)h[6];
+    // what the earlier parts hold of the list: their entries come first
+    int off = 0;
+    for (int q = tid; q < part; q += kPartThreads) off += c.hist[((int64_t)lz * c.parts + first + q) * kFirstDigitBins + b0];
+    off = part_sum(sh, off, 2);
+    int ab = 0, tb = 0;
+    constexpr int UNR = 8;
+    for (int i0 = tid; i0 < off; i0 += kPartThreads * UNR) {
+      uint32_t k[UNR];
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) k[u] = list[min(i0 + u * kPartThreads, off - 1)];
+#pragma unroll
+      for (int u = 0; u < UNR; ++u)
+        if (i0 + u * kPartThreads < off) { ab += k[u] > tau; tb += k[u] == tau; }
+    }
+    above_before = part_sum(sh, ab, 3);
+    __syncthreads();
+    ties_before = part_sum(sh, tb, 2);
+  }
+  int sure_before = 0;
+  for (int q = tid; q < part; q += kPartThreads) sure_before += c.sure[(int64_t)lz * c.parts + first + q];
+  __syncthreads();
+  sure_before = part_sum(sh, sure_before, 3) + above_before;
+  // classes of this thread's candidates: in whatever the cut / tied at the cut / out
+  unsigned in2 = 0, in1 = 0;
+  unsigned int cnt[kPartTiles], before[kPartTiles];
+#pragma unroll
+  for (int s = 0; s < kPartItems; ++s) {
+    const bool el = (elig >> s) & 1u, fo = (forc >> s) & 1u;
+    const bool two = fo || (el && mode == kModeSelect && keys[s] > tau);
+    const bool one = !fo && el && mode == kModeSelect && keys[s] == tau;
+    if (two) in2 |= 1u << s;
+    if (one) in1 |= 1u << s;
+  }
+#pragma unroll
+  for (int t = 0; t < kPartTiles; ++t) cnt[t] = __popc((in2 >> (4 * t)) & 15u) | (__popc((in1 >> (4 * t)) & 15u) << 16);
+  part_order(sh, cnt, before);
+#pragma unroll
+  for (int t = 0; t < kPartTiles; ++t) {
+    int ps = sure_before + (int)(before[t] & 0xFFFFu), pt = ties_before + (int)(before[t] >> 16);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int s = 4 * t + e, j = part_index(part, s);
+      const bool two = (in2 >> s) & 1u, one = (in1 >> s) & 1u;
+      if (j < npre) Rule::emit(a, lz, s0, o0, j, two || (one && pt < ties), ps + min(pt, ties), budget - a.W);
+      ps += two; pt += one;
+    }
+  }
+}
+
+// candidates kept in registers per thread by the one-workgroup kernels, chosen from the longest request
 static int items_for(const Plan& pl) {
   const int npre = pl.max_n - pl.W;
-  for (int items : {8, 16, 32, 48, 64})
-    if (npre <= kSelectThreads * items) return items;
-  return 0;
+  for (int items : {8, 16, 32, 48}) if (npre <= kSelectThreads * items) return items;
+  return 64;
 }
 
 #define CODECOMP_DISPATCH_ITEMS(KERNEL, GRID, ARGS)                                        \
@@ -447,14 +876,39 @@ static int items_for(const Plan& pl) {
     case 16: KERNEL<16><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
     case 32: KERNEL<32><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
     case 48: KERNEL<48><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
-    case 64: KERNEL<64><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
-    default: KERNEL<0><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;            \
+    default: KERNEL<64><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
   }
 
-int launch_select(const Plan& pl, const float* scores, int32_t* idx, hipStream_t stream) {
+static PartArgs part_args(const Plan& pl, void* workspace) {
+  char* ws = static_cast<char*>(workspace);
+  PartArgs c;
+  c.hist = reinterpret_cast<uint16_t*>(ws + pl.off_part_hist);
+  c.sure = reinterpret_cast<int32_t*>(ws + pl.off_part_sure);
+  c.head = reinterpret_cast<uint32_t*>(ws + pl.off_part_head);
+  c.list = reinterpret_cast<uint32_t*>(ws + pl.off_uraw);       // the raw attention mass is dead once the scores exist
+  c.parts = pl.sel_parts;
+  return c;
+}
+
+template <class Rule>
+static int launch_parts(const Plan& pl, const SelectArgs& a, const PartArgs& c, int lzs, hipStream_t stream) {
+  const dim3 grid(pl.sel_parts, lzs), block(kPartThreads);
+  part_counts_kernel<Rule><<<grid, block, 0, stream>>>(a, c);
+  if (hipError_t e = hipGetLastError()) return (int)e;
+  part_near_kernel<Rule><<<grid, block, 0, stream>>>(a, c);
+  if (hipError_t e = hipGetLastError()) return (int)e;
+  part_resolve_kernel<<<dim3(pl.n_seqs, lzs), block, 0, stream>>>(a, c);
+  if (hipError_t e = hipGetLastError()) return (int)e;
+  part_emit_kernel<Rule><<<grid, block, 0, stream>>>(a, c);
+  if (hipError_t e = hipGetLastError()) return (int)e;
+  return 0;
+}
+
+int launch_select(const Plan& pl, const float* scores, int32_t* idx, void* workspace, hipStream_t stream) {
   SelectArgs a = {};
   a.scores = scores; a.cu_seqlens = pl.cu_seqlens_dev; a.cu_budgets = pl.cu_budgets_dev; a.idx = idx;
   a.n_seqs = pl.n_seqs; a.T = pl.T; a.TB = pl.TB; a.W = pl.W;
+  if (pl.sel_parts > 0) return launch_parts<RuleAdditive>(pl, a, part_args(pl, workspace), pl.L * pl.Hkv, stream);
   CODECOMP_DISPATCH_ITEMS(select_kernel, dim3(pl.n_seqs, pl.L * pl.Hkv), a)
   if (hipError_t e = hipGetLastError()) return (int)e;
   return 0;
@@ -469,6 +923,11 @@ int launch_select_two_stage(const Plan& pl, const float* scores, const float* pr
   a.member_count = reinterpret_cast<int32_t*>(ws + pl.off_member_count);
   a.n_seqs = pl.n_seqs; a.T = pl.T; a.TB = pl.TB; a.W = pl.W;
   a.span_ratio = pl.span_ratio; a.span_min = pl.span_min;
+  if (pl.sel_parts > 0) {
+    const PartArgs c = part_args(pl, workspace);
+    if (int rc = launch_parts<RuleStage1>(pl, a, c, 1, stream)) return rc;
+    return launch_parts<RuleStage2>(pl, a, c, pl.L * pl.Hkv, stream);
+  }
   CODECOMP_DISPATCH_ITEMS(select_stage1_kernel, dim3(pl.n_seqs), a)
   if (hipError_t e = hipGetLastError()) return (int)e;
   CODECOMP_DISPATCH_ITEMS(select_stage2_kernel, dim3(pl.n_seqs, pl.L * pl.Hkv), a)

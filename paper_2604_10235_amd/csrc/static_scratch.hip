@@ -53,7 +53,7 @@ extern "C" int codecomp_compress_static(const void* q_obs, const void* k, const 
   if (pl.select_mode == CODECOMP_SELECT_TWO_STAGE) {
     if (int rc = launch_select_two_stage(pl, scores, prior, idx, ws, s)) return rc;
   } else {
-    if (int rc = launch_select(pl, scores, idx, s)) return rc;
+    if (int rc = launch_select(pl, scores, idx, ws, s)) return rc;
   }
   return launch_gather(pl, k, v, idx, k_out, v_out, s);
 }

@@ -72,14 +72,20 @@ def select_on_device(rows, seqlens, budgets, layers=1):
     return idx.cpu().numpy(), cu, cb
 
 
-# candidates per request -> the kernel keeps 8 / 16 / 32 / 48 / 64 of them per thread in registers, or streams them
-@pytest.mark.parametrize("npre,need", [(3000, 200), (9000, 1000), (30000, 2000), (40000, 3100), (60000, 4096),
-                                       (70000, 5000), (140000, 13043), (9000, 8999), (9000, 1)])
-def test_select_on_crafted_scores(npre, need):
+# Which kernels run depends on the longest request and on the number of (layer, head, request) problems: with 26
+# problems (2 layers x 13 rows) requests of 16384 candidates or more are cut into parts of 8192 (2, 3, 4, 5, 8, 9, 18
+# parts here, including the budgets that keep nothing or everything); with 104 problems (8 layers) one workgroup per
+# problem keeps 8 / 16 / 32 / 48 / 64 candidates per thread in registers up to 65536 candidates, parts beyond.
+@pytest.mark.parametrize("npre,need,layers", [
+    (3000, 200, 2), (9000, 1000, 2), (16383, 5000, 2), (16384, 5000, 2), (30000, 2000, 2), (40000, 3100, 2),
+    (60000, 4096, 2), (70000, 5000, 2), (140000, 13043, 2), (9000, 8999, 2), (9000, 1, 2), (20000, 20000, 2),
+    (20000, 0, 2), (20000, 19999, 2), (20000, 1, 2), (65536, 8192, 2),
+    (9000, 1000, 8), (30000, 2000, 8), (40000, 3100, 8), (60000, 4096, 8), (65536, 8192, 8), (65537, 8192, 8)])
+def test_select_on_crafted_scores(npre, need, layers):
     rows = crafted_rows(npre, need, seed=npre + need)
-    idx, cu, cb = select_on_device(rows, [npre + W], [need + W], layers=2)
+    idx, cu, cb = select_on_device(rows, [npre + W], [need + W], layers=layers)
     want = orc.select(rows.astype(np.float64), W, need + W)
-    for l in range(2):
+    for l in range(layers):
         assert np.array_equal(idx[l].astype(np.int64), want), (npre, need, l)
 
 
@@ -91,6 +97,20 @@ def test_select_on_crafted_scores_ragged():
     parts = [crafted_rows(n - W, max(1, b), seed=17 + i) if n > W else np.zeros((13, W), np.float32)
              for i, (n, b) in enumerate(zip(lens, needs))]
     rows = np.concatenate(parts, axis=1)
+    idx, cu, cb = select_on_device(rows, lens, [b + W for b in needs])
+    want = orc.select_packed(rows.astype(np.float64)[None], cu, cb, W)
+    assert np.array_equal(idx.astype(np.int64), want)
+
+
+def test_select_by_parts_in_a_batch_of_many_requests():
+    """One long request among 600 short ones: the whole batch is selected by parts (most requests are a single part,
+    some have no candidate at all), and a workgroup finds its request among many."""
+    g = np.random.default_rng(99)
+    lens = [int(x) + W for x in g.integers(0, 700, size=600)]
+    lens[0] = W; lens[599] = W + 1; lens[311] = 40000 + W; lens[312] = 17000 + W
+    needs = [int(g.integers(0, n - W + 1)) for n in lens]
+    rows = np.concatenate([crafted_rows(n - W, max(1, b), seed=1000 + i)[[(i + k_) % 13 for k_ in range(3)]] if n > W
+                           else np.zeros((3, W), np.float32) for i, (n, b) in enumerate(zip(lens, needs))], axis=1)
     idx, cu, cb = select_on_device(rows, lens, [b + W for b in needs])
     want = orc.select_packed(rows.astype(np.float64)[None], cu, cb, W)
     assert np.array_equal(idx.astype(np.int64), want)
