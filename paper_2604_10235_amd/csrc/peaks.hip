@@ -29,11 +29,9 @@ typedef struct codecomp_peaks {
   double mix_clock_mhz;
   double copy_gbs;              /* (bytes read + bytes written) / time of the copy pass               */
   double read_gbs;              /* bytes read / time of the read-only pass                            */
-  double mix_cycles_per_mfma;   /* shader cycles a SIMD spends per MFMA (with its two logits of softmax work per lane) */
   int32_t mix_waves_per_simd;
   int32_t compute_units;
   int32_t status;               /* 0 or the hipError_t that stopped the measurement                   */
-  int32_t pad_;
 } codecomp_peaks;
 }
 
@@ -207,7 +205,6 @@ extern "C" int codecomp_measure_peaks(const void* rnd, void* buf_a, void* buf_b,
     (void)hipMemcpyAsync(cyc, clk, 16, hipMemcpyDeviceToHost, s); (void)hipStreamSynchronize(s);
     out->mix_logits_per_s = (double)g * (kThreads / 64) * tiles * 64.0 * 64.0 / (ms * 1e-3);   // 64 keys x 64 rows per wave and tile
     out->mix_clock_mhz = cyc[1] > 0 ? (double)cyc[0] / ((double)cyc[1] * 1e-8) / 1e6 : 0.0;
-    out->mix_cycles_per_mfma = (double)cyc[0] / tiles / 32.0 * out->mix_waves_per_simd;          // shader cycles per MFMA slot of a SIMD
   }
   {
     const size_t n16 = bytes / 16;

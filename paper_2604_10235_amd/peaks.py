@@ -19,8 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libcodecomp_peaks.so")
 class codecomp_peaks(C.Structure):
     _fields_ = [("mfma_bf16_tflops", C.c_double), ("mfma_clock_mhz", C.c_double), ("exp_per_s", C.c_double),
                 ("fma_per_s", C.c_double), ("mix_logits_per_s", C.c_double), ("mix_clock_mhz", C.c_double),
-                ("copy_gbs", C.c_double), ("read_gbs", C.c_double), ("mix_cycles_per_mfma", C.c_double),
-                ("mix_waves_per_simd", C.c_int32), ("compute_units", C.c_int32), ("status", C.c_int32), ("pad_", C.c_int32)]
+                ("copy_gbs", C.c_double), ("read_gbs", C.c_double),
+                ("mix_waves_per_simd", C.c_int32), ("compute_units", C.c_int32), ("status", C.c_int32)]
 
 
 _state = {}
@@ -52,7 +52,9 @@ def measure(copy_bytes: int = 1 << 30) -> dict:
     return {"mfma_bf16_tflops": round(out.mfma_bf16_tflops, 1), "mfma_clock_mhz": round(out.mfma_clock_mhz),
             "exp_per_s": float(f"{out.exp_per_s:.4g}"), "fma_per_s": float(f"{out.fma_per_s:.4g}"),
             "mix_logits_per_s": float(f"{out.mix_logits_per_s:.4g}"), "mix_clock_mhz": round(out.mix_clock_mhz),
-            "mix_cycles_per_mfma": round(out.mix_cycles_per_mfma, 1), "mix_waves_per_simd": out.mix_waves_per_simd,
+            # shader cycles a SIMD spends per MFMA and its 128 logits of softmax work, from the rate and the clock
+            "mix_cycles_per_mfma": round(out.mix_clock_mhz * 1e6 * out.compute_units * 4 * 128 / out.mix_logits_per_s, 1)
+            if out.mix_logits_per_s > 0 else None, "mix_waves_per_simd": out.mix_waves_per_simd,
             "copy_gb_per_s": round(out.copy_gbs, 1), "read_gb_per_s": round(out.read_gbs, 1),
             "compute_units": out.compute_units}
 
