@@ -16,7 +16,8 @@ constexpr int kMinTilesPerWorkgroup = 4;
 constexpr int kLeadTiles = 4;         // a segment start (query fragments, first K tile) costs about this many tiles
 constexpr int kSelectThreads = 1024;  // one workgroup per (layer, head, request) in select, for short requests
 // Longer requests are selected by several workgroups each: parts of kPartChunk candidates, one 256-thread workgroup
-// per part and step (three steps: first-digit counts, the candidates near the cut, the ordered output).
+// per part and step (first-digit counts, the candidates near the cut, the ordered output; between the last two one
+// workgroup per request finishes the radix select on those candidates).
 constexpr int kPartThreads = 256;
 constexpr int kPartItems = 32;                             // candidates a thread holds
 constexpr int kPartChunk = kPartThreads * kPartItems;      // candidates per part

@@ -8,12 +8,13 @@
 // indices already sorted.  No float is ever added, nothing depends on the order in which workgroups run:
 // the result is the same bits on every call.
 //
-// Requests of at most 65536 candidates in a batch with enough problems to occupy the device: one workgroup of 1024 threads owns one
-// (layer, head, request) problem; the candidates are read from memory once, all loads in flight together,
-// and stay in registers through the three digit passes and the ordered pass.
-// A batch with a longer request, or with few problems and long requests: every request is cut into parts of 8192 candidates and four kernels run
-// one 256-thread workgroup per part (the third one per request), so that a problem is spread over as many compute units as it has parts
-// and a ragged batch is not paced by its longest request:
+// Requests of at most 65536 candidates in a batch with enough problems to occupy the device: one workgroup
+// of 1024 threads owns one (layer, head, request) problem; the candidates are read from memory once, all
+// loads in flight together, and stay in registers through the three digit passes and the ordered pass.
+// A batch with a longer request, or with few problems and long requests: every request is cut into parts
+// of 8192 candidates and four kernels run one 256-thread workgroup per part (the third one per request),
+// so that a problem is spread over as many compute units as it has parts and a ragged batch is not paced
+// by its longest request:
 //   counts  every part counts the first digit of its candidates (2048 bins) and stores the counts;
 //   near    every part adds up the counts of its request, finds the bin that holds the cut, and appends its
 //           candidates of that bin (keys only, in token order) to the request's list, at the place the
@@ -29,8 +30,9 @@
 //                (sections "Span-Level Structural Protection" and "Attention-based KV Cache
 //                Compression"): stage 1 keeps up to B_span = min(Bp, max(B_min, floor(rho * Bp)))
 //                prefix tokens with prior > 0, largest prior first (ties: first in sequence, which for a
-//                binary prior is the paper's rule for an overfull protected set: its first tokens), Bp = B - W; stage 2 fills the remaining
-//                Bp - |P| slots with the best pooled-attention tokens not in P.
+//                binary prior is the paper's rule for an overfull protected set: its first tokens),
+//                Bp = B - W; stage 2 fills the remaining Bp - |P| slots with the best pooled-attention
+//                tokens not in P.
 #include "plan.h"
 
 namespace codecomp {
@@ -389,7 +391,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_stage2_kernel(SelectArg
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Selection by parts: several workgroups per problem, three kernels (see the head of this file).
+// Selection by parts: several workgroups per problem, four kernels (see the head of this file).
 // ---------------------------------------------------------------------------------------------------------
 
 struct PartArgs {
