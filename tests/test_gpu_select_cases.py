@@ -116,6 +116,62 @@ def test_select_by_parts_in_a_batch_of_many_requests():
     assert np.array_equal(idx.astype(np.int64), want)
 
 
+def two_stage_on_device(rows, prior, seqlens, budgets, ratio, bmin, layers=1):
+    """rows [H][T] fp32 (pooled attention), prior [T] -> idx [L][H][TB] through codecomp_select_two_stage."""
+    import torch
+    from paper_2604_10235_amd import binding as b
+    h, total = rows.shape
+    cu = np.concatenate([[0], np.cumsum(seqlens)]).astype(np.int32)
+    cb = np.concatenate([[0], np.cumsum(budgets)]).astype(np.int32)
+    dev = torch.device("cuda:0")
+    cu_d, cb_d = torch.from_numpy(cu).to(dev), torch.from_numpy(cb).to(dev)
+    p = b.make_params(n_layers=layers, n_q_heads=h, n_kv_heads=h, head_dim=128, window=W, pool_kernel=1, prior_weight=0.0,
+                      cu_seqlens_host=cu, cu_budgets_host=cb, cu_seqlens_dev=cu_d.data_ptr(), cu_budgets_dev=cb_d.data_ptr(),
+                      select_mode=1, span_budget_ratio=ratio, span_budget_min=bmin)
+    sc = torch.from_numpy(np.broadcast_to(rows, (layers, h, total)).copy()).to(dev)
+    pr = torch.from_numpy(prior.astype(np.float32)).to(dev)
+    idx = torch.full((layers, h, int(cb[-1])), -7, dtype=torch.int32, device=dev)
+    ws = torch.empty(max(256, b.codecomp_workspace_bytes(p)), dtype=torch.uint8, device=dev)
+    ws.fill_(0xFF)
+    b.codecomp_select_two_stage(sc, pr, p, idx, ws)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), cu, cb
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_batches_with_long_requests(seed):
+    """Seeded random batches that hold at least one long request (so that the selection runs by parts), budgets from
+    the window alone to everything, scores with many ties; the additive rule and the two-stage rule (graded or binary
+    prior, any span budget) against the oracle's rules on the same fp32 values."""
+    g = np.random.default_rng(31000 + seed)
+    n_seqs = int(g.integers(1, 7))
+    lens = [W + int(g.integers(0, 3000)) for _ in range(n_seqs)]
+    lens[int(g.integers(0, n_seqs))] = W + int(g.choice([16384, 20000, 33333, 65536, 65537, 90000]))
+    if g.random() < 0.5:
+        lens.append(W + int(g.integers(16384, 40000)))
+    needs = [int(g.choice([0, 1, (n - W) // 10, (n - W) // 2, max(0, n - W - 1), n - W])) for n in lens]
+    total = sum(lens)
+    kind = int(g.integers(0, 3))
+    if kind == 0:
+        rows = g.random((3, total)).astype(np.float32)                                   # (almost) no ties
+    elif kind == 1:
+        rows = np.round(g.standard_normal((3, total)), 1).astype(np.float32)              # ~60 values, both signs
+    else:
+        rows = (g.integers(0, 3, size=(3, total)) * np.float32(0.25)).astype(np.float32)  # three values
+    budgets = [b + W for b in needs]
+    idx, cu, cb = select_on_device(rows, lens, budgets)
+    assert np.array_equal(idx.astype(np.int64), orc.select_packed(rows.astype(np.float64)[None], cu, cb, W))
+    # the two-stage rule on the same scores
+    prior = np.where(g.random(total) < g.choice([0.05, 0.3, 0.9]), g.random(total) if g.random() < 0.5 else 1.0, 0.0).astype(np.float32)
+    ratio, bmin = float(g.choice([0.0, 0.25, 0.5, 1.0])), int(g.choice([0, 7, 5000]))
+    idx2, _, _ = two_stage_on_device(rows, prior, lens, budgets, ratio, bmin)
+    for r in range(len(lens)):
+        a, e = cu[r], cu[r + 1]
+        want = orc.select_two_stage(rows[:, a:e].astype(np.float64), prior[a:e], W, budgets[r],
+                                    span_ratio=float(np.float32(ratio)), span_min=bmin)
+        assert np.array_equal(idx2[0, :, cb[r]:cb[r + 1]].astype(np.int64), want), (seed, r, lens[r], budgets[r], ratio, bmin)
+
+
 def two_stage_full(w, ratio=0.5, bmin=0, layers_checked=None):
     """Fused call in two-stage mode on a full-size workload; indices bit-equal to the oracle's two-stage rule on the
     GPU's own fp32 scores (every layer in `layers_checked`, every head, every request), gather bit-exact."""
