@@ -92,7 +92,8 @@ typedef struct codecomp_params {
   /* How the two logit passes of codecomp_score are cut into workgroups; the results do not depend on either
    * value beyond the regrouping of fp32 sums (for tests of exactly that, and for tuning).  Leave both 0. */
   int32_t score_workgroups;    /* 0 = as many as the device holds at once; n > 0 = n (at most 2048, at most one per
-                                  64-key tile)                                                       */
+                                  64-key tile; with more than 512 softmax rows per KV head the rows are split over
+                                  teams of workgroups and n is rounded down to whole teams)          */
   int32_t score_lead_tiles;    /* weight, in 64-key tiles, given to the start of a request when the tiles are shared
                                   out: 0 = built-in value, < 0 = none, 1..64 = that many             */
 } codecomp_params;
