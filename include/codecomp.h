@@ -181,7 +181,8 @@ int codecomp_score_stages(const void* q_obs, const void* k, const float* prior, 
  * prefix [0, N_r - W) with the largest scores (equal scores: the lower index wins; scores are
  * ordered as IEEE floats, -0 == +0, NaN unspecified), write the B_r indices in ascending
  * order.  Follows section "Attention-based KV Cache Compression": the best-scored context tokens are kept
- * until the remaining budget of the chunk is used up. */
+ * until the remaining budget of the chunk is used up.  workspace (>= codecomp_workspace_bytes(), 256-byte aligned)
+ * is scratch for long requests, which several workgroups select together; its contents on entry do not matter. */
 int codecomp_select(const float* scores, const codecomp_params* params, int32_t* idx,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
