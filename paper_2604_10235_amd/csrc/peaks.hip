@@ -14,26 +14,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "codecomp_peaks.h"
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 #define BC(a) __builtin_bit_cast(bf16x8, a)
-
-extern "C" {
-typedef struct codecomp_peaks {
-  double mfma_bf16_tflops;      /* dense bf16 MFMA, random operands                                   */
-  double mfma_clock_mhz;        /* shader clock during that run                                       */
-  double exp_per_s;             /* v_exp_f32 results per second, whole chip                           */
-  double fma_per_s;             /* v_fma_f32 results per second, whole chip                           */
-  double mix_logits_per_s;      /* logits per second through (half an MFMA at d = 128) + fma + exp2 + add */
-  double mix_clock_mhz;
-  double copy_gbs;              /* (bytes read + bytes written) / time of the copy pass               */
-  double read_gbs;              /* bytes read / time of the read-only pass                            */
-  int32_t mix_waves_per_simd;
-  int32_t compute_units;
-  int32_t status;               /* 0 or the hipError_t that stopped the measurement                   */
-} codecomp_peaks;
-}
 
 namespace {
 
@@ -149,10 +135,6 @@ __global__ __launch_bounds__(kThreads) void read_kernel(const u32x4* __restrict_
 
 }  // namespace
 
-// rnd: device, >= 64 KiB of bf16 bit patterns of random numbers (operands of the MFMA runs), 16-byte aligned.
-// buf_a, buf_b: device, `bytes` bytes each (copy source and destination; bytes a multiple of 16, several times the
-// 256 MB memory-side cache for a figure that means HBM).  small: device, >= 64 bytes (sink and cycle counts).
-// Synchronises the stream (this is a measurement, not a hot-path call).  Returns 0 or a hipError_t.
 extern "C" int codecomp_measure_peaks(const void* rnd, void* buf_a, void* buf_b, size_t bytes, void* small,
                                       codecomp_peaks* out, void* hip_stream) {
   if (!rnd || !buf_a || !buf_b || !small || !out || bytes < (1u << 20) || (bytes & 15)) return -1;

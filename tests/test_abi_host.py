@@ -36,6 +36,36 @@ def test_every_declared_symbol_is_exported():
         assert hasattr(lib, n), n
 
 
+def test_peaks_library_exports_its_declared_symbol():
+    from paper_2604_10235_amd import peaks
+    text = open(os.path.join(ROOT, "include", "codecomp_peaks.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(codecomp_[a-z_]+)\s*\(", text)))
+    assert names == ["codecomp_measure_peaks"]
+    lib = C.CDLL(peaks.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    # 8 doubles and 3 int32 (+ padding to 8): the binding's mirror of the struct
+    assert C.sizeof(peaks.codecomp_peaks) == 8 * 8 + 16 and peaks.codecomp_peaks.mix_waves_per_simd.offset == 64
+    # bad arguments are refused on the host
+    lib.codecomp_measure_peaks.restype = C.c_int
+    lib.codecomp_measure_peaks.argtypes = [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
+    out = peaks.codecomp_peaks()
+    assert lib.codecomp_measure_peaks(None, 0x1000, 0x1000, 1 << 20, 0x1000, C.byref(out), None) == -1
+    assert lib.codecomp_measure_peaks(0x1000, 0x1000, 0x1000, 1000, 0x1000, C.byref(out), None) == -1
+
+
+def test_selection_by_parts_shows_in_the_workspace_size():
+    # a request beyond 65536 candidates (or a long one among few problems) is selected by parts of 8192 candidates:
+    # 2048 16-bit counts per (layer * head, part)
+    def ws(n, layers):
+        return b.codecomp_workspace_bytes(good(n_layers=layers, cu_seqlens_host=np.array([0, n]), cu_budgets_host=np.array([0, 100])))
+    few, many = 2, 60                                    # 2 KV heads: 4 and 120 (layer, head, request) problems
+    assert ws(16 + 16384, few) - ws(16 + 16383, few) >= few * 2 * 2 * 2048 * 2           # two parts from 16384 candidates on
+    assert ws(16 + 16384, many) - ws(16 + 16383, many) < 4096 * many                      # many problems: one workgroup each
+    assert ws(16 + 65537, many) - ws(16 + 65536, many) >= many * 2 * 9 * 2048 * 2         # nine parts beyond 65536
+
+
 def test_struct_layout_matches_header():
     # 10 x 4-byte fields, 4 pointers, 10 x int64 strides, span budget (float + int32), variant flags + kv_dtype,
     # the two launch-shape fields
