@@ -585,8 +585,9 @@ __device__ __forceinline__ void part_order(PartShared& sh, const unsigned int (&
   __syncthreads();
 }
 
+template <int NT = kPartThreads>
 __device__ __forceinline__ void part_hist_clear(PartShared& sh, int nbins) {
-  for (int b = threadIdx.x; b < (kPartCopies - 1) * kHistStride + nbins; b += kPartThreads) sh.hist[b] = 0;
+  for (int b = threadIdx.x; b < (kPartCopies - 1) * kHistStride + nbins; b += NT) sh.hist[b] = 0;
   __syncthreads();
 }
 
@@ -719,24 +720,26 @@ __global__ __launch_bounds__(kPartThreads) void part_near_kernel(SelectArgs a, P
   }
 }
 
-// One more digit of the radix select over the request's list (all threads call it).  Entries whose bits above the
-// digit equal `prefix` take part; afterwards `prefix` has the digit filled in and `remaining` is the rank inside it.
+// One more digit of the radix select over the request's list (all NT threads of the workgroup call it).  Entries whose
+// bits above the digit equal `prefix` take part; afterwards `prefix` has the digit filled in and `remaining` is the
+// rank inside it.
+template <int NT>
 __device__ __forceinline__ void part_digit(PartShared& sh, const uint32_t* list, int m, int shift, int nbins, uint32_t himask,
                                            uint32_t& prefix, uint32_t& remaining) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  part_hist_clear(sh, nbins);
+  part_hist_clear<NT>(sh, nbins);
   constexpr int UNR = 8;                                  // loads in flight per thread
-  for (int i0 = tid; i0 < m; i0 += kPartThreads * UNR) {
+  for (int i0 = tid; i0 < m; i0 += NT * UNR) {
     uint32_t k[UNR];
 #pragma unroll
-    for (int u = 0; u < UNR; ++u) k[u] = list[min(i0 + u * kPartThreads, m - 1)];
+    for (int u = 0; u < UNR; ++u) k[u] = list[min(i0 + u * NT, m - 1)];
 #pragma unroll
     for (int u = 0; u < UNR; ++u)
-      if (i0 + u * kPartThreads < m && (k[u] & himask) == prefix)
+      if (i0 + u * NT < m && (k[u] & himask) == prefix)
         atomicAdd(&sh.hist[(tid & (kPartCopies - 1)) * kHistStride + ((k[u] >> shift) & (uint32_t)(nbins - 1))], 1u);
   }
   __syncthreads();
-  for (int b = tid; b < nbins; b += kPartThreads) {
+  for (int b = tid; b < nbins; b += NT) {
     unsigned int t = 0;
 #pragma unroll
     for (int k = 0; k < kPartCopies; ++k) t += sh.hist[k * kHistStride + b];
@@ -771,7 +774,8 @@ __device__ __forceinline__ void part_digit(PartShared& sh, const uint32_t* list,
 
 // resolve: one workgroup per problem finishes the radix select on the request's list (two more digits) and leaves
 // the key of the cut and the number of candidates tied at it that are admitted.
-__global__ __launch_bounds__(kPartThreads) void part_resolve_kernel(SelectArgs a, PartArgs c) {
+constexpr int kResolveThreads = 1024;     // the list is read with 8 loads in flight per thread: many threads, few rounds
+__global__ __launch_bounds__(kResolveThreads) void part_resolve_kernel(SelectArgs a, PartArgs c) {
   __shared__ PartShared sh;
   const int seq = blockIdx.x, lz = blockIdx.y;
   uint32_t* h = c.head + ((int64_t)lz * a.n_seqs + seq) * 8;
@@ -779,8 +783,8 @@ __global__ __launch_bounds__(kPartThreads) void part_resolve_kernel(SelectArgs a
   const uint32_t* list = c.list + (int64_t)lz * a.T + a.cu_seqlens[seq];
   const int m = (int)h[3];
   uint32_t prefix = h[1] << 21, remaining = h[2];
-  part_digit(sh, list, m, 10, 2048, 0xFFE00000u, prefix, remaining);
-  part_digit(sh, list, m, 0, 1024, 0xFFFFFC00u, prefix, remaining);
+  part_digit<kResolveThreads>(sh, list, m, 10, 2048, 0xFFE00000u, prefix, remaining);
+  part_digit<kResolveThreads>(sh, list, m, 0, 1024, 0xFFFFFC00u, prefix, remaining);
   if (threadIdx.x == 0) { h[5] = prefix; h[6] = remaining; }
 }
 
@@ -899,7 +903,7 @@ static int launch_parts(const Plan& pl, const SelectArgs& a, const PartArgs& c, 
   if (hipError_t e = hipGetLastError()) return (int)e;
   part_near_kernel<Rule><<<grid, block, 0, stream>>>(a, c);
   if (hipError_t e = hipGetLastError()) return (int)e;
-  part_resolve_kernel<<<dim3(pl.n_seqs, lzs), block, 0, stream>>>(a, c);
+  part_resolve_kernel<<<dim3(pl.n_seqs, lzs), dim3(kResolveThreads), 0, stream>>>(a, c);
   if (hipError_t e = hipGetLastError()) return (int)e;
   part_emit_kernel<Rule><<<grid, block, 0, stream>>>(a, c);
   if (hipError_t e = hipGetLastError()) return (int)e;
