@@ -177,6 +177,7 @@ int make_plan(const codecomp_params* p, Plan* pl) {
     pl->off_part_hist = off; off = align256(off + LH * (size_t)parts * kFirstDigitBins * sizeof(uint16_t));
     pl->off_part_sure = off; off = align256(off + LH * (size_t)parts * sizeof(int32_t));
     pl->off_part_head = off; off = align256(off + LH * (size_t)pl->n_seqs * 8 * sizeof(uint32_t));
+    pl->off_part_before = off; off = align256(off + LH * (size_t)parts * 2 * sizeof(int32_t));
   }
   pl->ws_bytes = off;
   return CODECOMP_OK;

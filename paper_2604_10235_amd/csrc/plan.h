@@ -59,7 +59,7 @@ struct Plan {
   size_t off_stats, off_lse, off_uraw, off_member, off_member_count, ws_bytes;
   // selection by parts (0 parts: one workgroup per request does it all)
   int sel_parts;             // sum over requests of max(1, ceil((N_r - W) / kPartChunk))
-  size_t off_part_hist, off_part_sure, off_part_head;
+  size_t off_part_hist, off_part_sure, off_part_head, off_part_before;
 };
 
 // Spreads `row_blocks` blocks over the waves of a workgroup (fills waves, wave_desc, rb_holder).

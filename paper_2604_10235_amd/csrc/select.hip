@@ -398,8 +398,9 @@ struct PartArgs {
   uint16_t* hist;        // [lz][part][2048] first-digit counts of each part (at most kPartChunk each)
   int32_t* sure;         // [lz][part] candidates of the part admitted whatever the cut: bins above the cut's, forced ones
   uint32_t* head;        // [lz][request][8]: mode, first digit of the cut, rank of the cut inside that bin, size of that bin,
-                         //                   number of competing candidates admitted
+                         //                   number of competing candidates admitted, key of the cut, ties admitted, 1 if `before` is filled in
   uint32_t* list;        // [lz][T] keys of the candidates in the cut's bin, per request from its first token on, in token order
+  int32_t* before;       // [lz][part][2] candidates of the earlier parts in the cut's bin that lie above the cut / are tied at it
   int parts;             // parts of all requests together
 };
 
@@ -412,7 +413,7 @@ static_assert(kPartHistWords >= kPartCopies * kHistStride, "histogram storage of
 struct PartShared {
   unsigned int hist[kPartHistWords];
   unsigned int prefix, need;
-  int red[4][kPartThreads / 64];
+  int red[4][16];          // up to 16 waves (the resolve kernel)
   int found[4];
 };
 
@@ -785,7 +786,76 @@ __global__ __launch_bounds__(kResolveThreads) void part_resolve_kernel(SelectArg
   uint32_t prefix = h[1] << 21, remaining = h[2];
   part_digit<kResolveThreads>(sh, list, m, 10, 2048, 0xFFE00000u, prefix, remaining);
   part_digit<kResolveThreads>(sh, list, m, 0, 1024, 0xFFFFFC00u, prefix, remaining);
-  if (threadIdx.x == 0) { h[5] = prefix; h[6] = remaining; }
+  const uint32_t tau = prefix;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // How many list entries of each part lie above the cut / are tied at it, as running totals over the parts: an
+  // emitting part then knows what the earlier parts contribute without reading their stretch of the list again.
+  const int npre = a.cu_seqlens[seq + 1] - a.cu_seqlens[seq] - a.W;
+  const int nparts = parts_of(npre);
+  const bool fits = 3 * nparts <= kPartHistWords;            // else the emitting parts count for themselves
+  if (tid == 0) { h[5] = tau; h[6] = remaining; h[7] = fits ? 1u : 0u; }
+  if (!fits) return;                                         // the same for every thread
+  int mine = 0;                                              // number of this request's first part
+  for (int r = tid; r < seq; r += kResolveThreads) mine += parts_of(a.cu_seqlens[r + 1] - a.cu_seqlens[r] - a.W);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off);
+  if (lane == 0) sh.red[0][wave] = mine;
+  __syncthreads();
+  int first = 0;
+#pragma unroll
+  for (int w = 0; w < kResolveThreads / 64; ++w) first += sh.red[0][w];
+  unsigned int* seg_end = sh.hist;                           // end of each part's stretch of the list
+  unsigned int* n_above = sh.hist + nparts;
+  unsigned int* n_tied = sh.hist + 2 * nparts;
+  const int b0 = (int)h[1];
+  for (int q = tid; q < nparts; q += kResolveThreads) {
+    seg_end[q] = c.hist[((int64_t)lz * c.parts + first + q) * kFirstDigitBins + b0];
+    n_above[q] = 0; n_tied[q] = 0;
+  }
+  __syncthreads();
+  // running totals over the parts, 64 at a time, by the first wave: seg_end becomes the end offsets
+  auto running = [&](unsigned int* v, bool exclusive) __attribute__((always_inline)) {
+    if (wave == 0) {
+      unsigned int carry = 0;
+      for (int base = 0; base < nparts; base += 64) {
+        const unsigned int x = base + lane < nparts ? v[base + lane] : 0u;
+        unsigned int incl = x;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const unsigned int o = __shfl_up(incl, off);
+          if (lane >= off) incl += o;
+        }
+        if (base + lane < nparts) v[base + lane] = carry + (exclusive ? incl - x : incl);
+        carry += __shfl(incl, 63);
+      }
+    }
+    __syncthreads();
+  };
+  running(seg_end, false);
+  constexpr int UNR = 8;
+  for (int i0 = tid; i0 < m; i0 += kResolveThreads * UNR) {
+    uint32_t k[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) k[u] = list[min(i0 + u * kResolveThreads, m - 1)];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int i = i0 + u * kResolveThreads;
+      if (i >= m || k[u] < tau) continue;
+      int lo = 0, hi = nparts - 1;                           // first part whose stretch ends beyond i
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (seg_end[mid] > (unsigned int)i) hi = mid; else lo = mid + 1;
+      }
+      atomicAdd(k[u] > tau ? &n_above[lo] : &n_tied[lo], 1u);
+    }
+  }
+  __syncthreads();
+  running(n_above, true);
+  running(n_tied, true);
+  for (int q = tid; q < nparts; q += kResolveThreads) {
+    int32_t* out = c.before + ((int64_t)lz * c.parts + first + q) * 2;
+    out[0] = (int32_t)n_above[q]; out[1] = (int32_t)n_tied[q];
+  }
 }
 
 // emit: every part writes its admitted candidates at their final places.
@@ -820,19 +890,25 @@ __global__ __launch_bounds__(kPartThreads) void part_emit_kernel(SelectArgs a, P
     const uint32_t* list = c.list + (int64_t)lz * a.T + s0;
     tau = h[5];
     ties = (int)h[6];
-    // what the earlier parts hold of the list: their entries come first
-    int off = 0;
-    for (int q = tid; q < part; q += kPartThreads) off += c.hist[((int64_t)lz * c.parts + first + q) * kFirstDigitBins + b0];
-    off = part_sum(sh, off, 2);
     int ab = 0, tb = 0;
-    constexpr int UNR = 8;
-    for (int i0 = tid; i0 < off; i0 += kPartThreads * UNR) {
-      uint32_t k[UNR];
+    if (h[7] != 0u) {                                     // the resolve kernel has counted for every part
+      const int32_t* bf = c.before + ((int64_t)lz * c.parts + gp) * 2;
+      if (tid == 0) { ab = bf[0]; tb = bf[1]; }
+    } else {
+      // what the earlier parts hold of the list: their entries come first
+      int off = 0;
+      for (int q = tid; q < part; q += kPartThreads) off += c.hist[((int64_t)lz * c.parts + first + q) * kFirstDigitBins + b0];
+      off = part_sum(sh, off, 2);
+      constexpr int UNR = 8;
+      for (int i0 = tid; i0 < off; i0 += kPartThreads * UNR) {
+        uint32_t k[UNR];
 #pragma unroll
-      for (int u = 0; u < UNR; ++u) k[u] = list[min(i0 + u * kPartThreads, off - 1)];
+        for (int u = 0; u < UNR; ++u) k[u] = list[min(i0 + u * kPartThreads, off - 1)];
 #pragma unroll
-      for (int u = 0; u < UNR; ++u)
-        if (i0 + u * kPartThreads < off) { ab += k[u] > tau; tb += k[u] == tau; }
+        for (int u = 0; u < UNR; ++u)
+          if (i0 + u * kPartThreads < off) { ab += k[u] > tau; tb += k[u] == tau; }
+      }
+      __syncthreads();
     }
     above_before = part_sum(sh, ab, 3);
     __syncthreads();
@@ -892,6 +968,7 @@ static PartArgs part_args(const Plan& pl, void* workspace) {
   c.sure = reinterpret_cast<int32_t*>(ws + pl.off_part_sure);
   c.head = reinterpret_cast<uint32_t*>(ws + pl.off_part_head);
   c.list = reinterpret_cast<uint32_t*>(ws + pl.off_uraw);       // the raw attention mass is dead once the scores exist
+  c.before = reinterpret_cast<int32_t*>(ws + pl.off_part_before);
   c.parts = pl.sel_parts;
   return c;
 }
