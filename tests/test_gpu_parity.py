@@ -470,3 +470,24 @@ def test_random_valid_shapes(seed):
                   window=window, head_dim=d, n_kv_heads=h_kv, n_q_heads=h_kv * group,
                   pool_kernel=int(g.choice([1, 3, 5, 7, 9, 21])), prior_weight=float(g.choice([0.0, 0.5, 1.0, 3.0])))
     run_case(w, fused=bool(g.integers(0, 2)), variant=variant, kv=kv)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_batches_with_long_requests_end_to_end(seed):
+    """Like test_random_valid_shapes, but every batch holds a request long enough for the selection to run by parts
+    (few heads and a small window keep the oracle quick): score, select and gather against the oracle."""
+    g = np.random.default_rng(7700 + seed)
+    window = int(g.choice([16, 32, 64]))
+    n_seqs = int(g.integers(1, 4))
+    lens = [int(window + g.integers(0, 3000)) for _ in range(n_seqs)]
+    lens[int(g.integers(0, n_seqs))] = window + int(g.choice([16384, 20011, 40000, 70001]))
+    budgets = [int(g.choice([window, window + (n - window) // 16, window + (n - window) // 2, n])) for n in lens]
+    h_kv = int(g.integers(1, 3))
+    group = int(g.choice([1, 2, 4]))
+    kv = "fp8_e4m3" if g.random() < 0.3 else "bf16"
+    w = wl.scaled(wl.qwen7b_32k(), name=f"randlong{seed}", n_layers=1, seqlens=lens, budgets=budgets, window=window,
+                  head_dim=int(g.choice([64, 128])), n_kv_heads=h_kv, n_q_heads=h_kv * group,
+                  pool_kernel=int(g.choice([1, 5, 7])), prior_weight=float(g.choice([0.0, 1.0, 2.0])))
+    run_case(w, fused=bool(g.integers(0, 2)), kv=kv)
+    if seed % 2 == 0:
+        run_two_stage(w, float(g.choice([0.25, 0.5, 1.0])), int(g.choice([0, 100])), fused=True)
