@@ -89,6 +89,22 @@ def test_select_on_crafted_scores(npre, need, layers):
         assert np.array_equal(idx[l].astype(np.int64), want), (npre, need, l)
 
 
+def test_select_beyond_the_table_of_the_resolve_kernel():
+    """More parts than the resolve kernel can keep running totals for (3 * parts > its 8200 words: 2734 parts of 8192
+    candidates): the emitting parts then count the earlier parts' entries themselves."""
+    npre, need = 2734 * 8192 + 5, 1_000_003
+    g = np.random.default_rng(99)
+    n = npre + W
+    two = np.full(n, 0.25, np.float32)
+    two[g.choice(npre, size=need - need // 3, replace=False)] = 0.75           # the cut falls among millions of low ties
+    coarse = np.round(g.standard_normal(n), 1).astype(np.float32)               # ~60 distinct values
+    rows = np.stack([two, coarse, np.full(n, 0.5, np.float32)])
+    idx, cu, cb = select_on_device(rows, [n], [need + W])
+    for r in range(rows.shape[0]):
+        want = orc.select(rows[r:r + 1].astype(np.float64), W, need + W)[0]
+        assert np.array_equal(idx[0, r].astype(np.int64), want), r
+
+
 def test_select_on_crafted_scores_ragged():
     """Requests of very different lengths in one call (the longest one decides the kernel variant), budgets from the
     window alone to everything."""
