@@ -69,8 +69,8 @@ def test_llama8b_64k_all_layers():
 
 @pytest.mark.timeout(600)
 def test_long_128k_all_layers():
-    # all 28 layers; W = 128, G = 7: 896 rows in two row splits, budget partly forced by the prior, the streaming
-    # form of the selection; the oracle scores one head of the first, a middle and the last layer
+    # all 28 layers; W = 128, G = 7: 896 rows in two row splits, budget partly forced by the prior, selection
+    # by parts (16 parts per problem); the oracle scores one head of the first, a middle and the last layer
     run_full(wl.long_128k(), [(0, 1, 0), (14, 3, 0), (27, 0, 0)])
 
 
@@ -80,6 +80,6 @@ def test_qwen7b_32k_all_layers_fp8_cache():
 
 def test_one_million_tokens_in_one_request():
     # far beyond the configurations: 2**20 keys under one head (16384 tiles of one problem spread over the whole
-    # chip, the streaming form of the selection, 50000 kept rows)
+    # chip, selection by 128 parts, 50000 kept rows)
     w = wl.scaled(wl.qwen7b_32k(), n_layers=1, n_q_heads=2, n_kv_heads=1, window=32, seqlens=[1 << 20], budgets=[50000])
     run_full(w, [(0, 0, 0)])

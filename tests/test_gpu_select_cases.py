@@ -2,7 +2,7 @@
 
 * codecomp_select on crafted fp32 score rows uploaded straight into `scores` (no score step): equal rows, two
   values with thousands of ties at the cut, negatives, +-0, infinities, at candidate counts that reach every
-  register variant of the kernel and the streaming one - indices bit-equal to the oracle's rule.
+  register variant of the one-workgroup kernel and the selection by parts - indices bit-equal to the oracle's rule.
 * The two-stage rule at full request length for every variant: the 32K, ragged, 64K and 128K workloads.
 * Structure-aware budgets -> cu_budgets -> ragged compress -> oracle, end to end.
 """
@@ -228,7 +228,7 @@ def test_two_stage_llama8b_64k_two_layers():          # 64 per thread, binary pr
     two_stage_full(wl.scaled(wl.llama8b_64k(), n_layers=2))
 
 
-def test_two_stage_long_128k_one_layer():             # streaming form, binary prior, budget 13107
+def test_two_stage_long_128k_one_layer():             # selection by parts, binary prior, budget 13107
     two_stage_full(wl.scaled(wl.long_128k(), n_layers=1))
 
 
