@@ -491,3 +491,24 @@ def test_random_batches_with_long_requests_end_to_end(seed):
     run_case(w, fused=bool(g.integers(0, 2)), kv=kv)
     if seed % 2 == 0:
         run_two_stage(w, float(g.choice([0.25, 0.5, 1.0])), int(g.choice([0, 100])), fused=True)
+
+
+def test_readme_example_runs_as_written():
+    """The usage example of the README, taken from the file and executed: its marked tokens and its window are kept,
+    and the compact cache holds the rows the indices name."""
+    import os
+    import torch
+    text = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "README.md")).read()
+    start = text.index("    import numpy as np, torch")
+    end = text.index("Out of scope:")
+    code = "\n".join(line[4:] for line in text[start:end].splitlines())
+    ns = {}
+    exec(compile(code, "README.md", "exec"), ns)
+    torch.cuda.synchronize()
+    idx, k, k_out, N, W, B = ns["idx"].cpu().numpy(), ns["k"], ns["k_out"], ns["N"], ns["W"], ns["B"]
+    assert (np.diff(idx, axis=-1) > 0).all() and idx.min() >= 0 and idx.max() == N - 1
+    assert (idx[..., -W:] == np.arange(N - W, N)).all()
+    marked = np.arange(100, 140)
+    assert all(np.isin(marked, idx[l, h]).all() for l in range(idx.shape[0]) for h in range(idx.shape[1]))
+    want = torch.gather(k, 2, ns["idx"].long().unsqueeze(-1).expand(-1, -1, -1, k.shape[-1]))
+    assert torch.equal(k_out, want)
