@@ -15,6 +15,9 @@ constexpr int kMaxScoreGrid = 2048;   // most workgroups a score pass is launche
 constexpr int kMinTilesPerWorkgroup = 4;
 constexpr int kLeadTiles = 4;         // a segment start (query fragments, first K tile) costs about this many tiles
 constexpr int kSelectThreads = 1024;  // one workgroup per (layer, head, request) in select, for short requests
+constexpr int kSelectSmallThreads = 256;    // ... and in batches of many requests of at most 256 x 16 candidates
+constexpr int kSelectSmallMaxItems = 16;
+constexpr int kSelectSmallProblems = 1024;  // problems from which on the small workgroups are used
 // Longer requests are selected by several workgroups each: parts of kPartChunk candidates, one 256-thread workgroup
 // per part and step (first-digit counts, the candidates near the cut, the ordered output; between the last two one
 // workgroup per request finishes the radix select on those candidates).

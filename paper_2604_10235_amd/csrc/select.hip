@@ -9,8 +9,9 @@
 // the result is the same bits on every call.
 //
 // Requests of at most 65536 candidates in a batch with enough problems to occupy the device: one workgroup
-// of 1024 threads owns one (layer, head, request) problem; the candidates are read from memory once, all
-// loads in flight together, and stay in registers through the three digit passes and the ordered pass.
+// of 1024 threads (256 threads when all requests are short and there are a thousand problems or more) owns one
+// (layer, head, request) problem; the candidates are read from memory once, all loads in flight together, and
+// stay in registers through the three digit passes and the ordered pass.
 // A batch with a longer request, or with few problems and long requests: every request is cut into parts
 // of 8192 candidates and four kernels run one 256-thread workgroup per part (the third one per request),
 // so that a problem is spread over as many compute units as it has parts and a ragged batch is not paced
@@ -45,31 +46,38 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 }
 
 constexpr int kSelTileItems = 4;    // consecutive candidates per thread inside one ordered tile
-constexpr int kSelMaxItems = kSelectMaxCandidates / kSelectThreads;   // most candidates a thread of the one-workgroup kernels holds
-constexpr int kSelTile = kSelectThreads * kSelTileItems;
-
-constexpr int kHistCopies = 8;      // private copies of the first-digit histogram, picked by lane % 8
 constexpr int kHistStride = 2049;   // odd stride: equal bins of different copies sit in different banks
 
-struct SelectShared {
-  unsigned int hist[kHistCopies * kHistStride];
+// The one-workgroup kernels come in two sizes.  NT = 1024 threads, up to 64 candidates per thread, 8 private copies of
+// the first-digit histogram (130 KB of LDS: one workgroup per compute unit) for long requests; NT = 256 threads, up to
+// 16 candidates per thread, 2 copies (21 KB: seven workgroups per compute unit) for batches of many short requests,
+// where what counts is how many problems a compute unit works on at once (measured on 7168 problems of 14 .. 2185
+// candidates: 270 us with the large workgroups, 132 / 105 / 108 us with the small ones and 4 / 2 / 1 copies; from
+// 8192 candidates per problem on the large ones are faster).
+template <int NT> struct SelectSize {
+  static constexpr int kMaxItems = NT == kSelectThreads ? kSelectMaxCandidates / kSelectThreads : kSelectSmallMaxItems;
+  static constexpr int kCopies = NT == kSelectThreads ? 8 : 2;     // picked by lane % kCopies
+};
+
+template <int NT> struct SelectShared {
+  unsigned int hist[SelectSize<NT>::kCopies * kHistStride];
   unsigned int prefix, need;
-  int wave_sure[kSelectThreads / 64], wave_tie[kSelectThreads / 64];
+  int wave_sure[NT / 64], wave_tie[NT / 64];
   int tile_sure, tile_tie;
   // class (0 out, 1 tied at the cut, 2 in) of every register-resident candidate, one byte each, indexed by
   // candidate: written in the load layout, read back as runs of consecutive candidates per thread
-  unsigned int cls_words[kSelectThreads * kSelMaxItems / 4];
+  unsigned int cls_words[NT * SelectSize<NT>::kMaxItems / 4];
 };
 
 // One candidate into the digit histogram.  CROWDED (the first digit: every candidate takes part and the scores
 // crowd into a few dozen bins): LDS atomics of one instruction that hit the same address are served one after
-// the other, so each lane adds to one of kHistCopies private copies (lane % 8) and at most 8 lanes can collide;
+// the other, so each lane adds to one of several private copies (lane % copies) and fewer lanes can collide;
 // the copies are summed when the bin is picked.  Ballot-based aggregation was tried first: its serial
 // scalar/vector control flow cost about 1000 cycles per candidate slot and workgroup.  Later digits: only the
 // few candidates that share the prefix take part, one copy.
-template <bool CROWDED>
-__device__ __forceinline__ void hist_add(SelectShared& sh, bool match, uint32_t bin) {
-  if (match) atomicAdd(&sh.hist[(CROWDED ? (threadIdx.x & (kHistCopies - 1)) * kHistStride : 0) + bin], 1u);
+template <bool CROWDED, int NT>
+__device__ __forceinline__ void hist_add(SelectShared<NT>& sh, bool match, uint32_t bin) {
+  if (match) atomicAdd(&sh.hist[(CROWDED ? (threadIdx.x & (SelectSize<NT>::kCopies - 1)) * kHistStride : 0) + bin], 1u);
 }
 
 __device__ __forceinline__ int pass_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
@@ -78,8 +86,9 @@ __device__ __forceinline__ uint32_t pass_himask(int pass) {
   return pass == 0 ? 0u : (0xFFFFFFFFu << (pass == 1 ? 21 : 10));
 }
 
-__device__ __forceinline__ void hist_clear(SelectShared& sh, int nbins, int copies) {
-  for (int b = threadIdx.x; b < (copies - 1) * kHistStride + nbins; b += kSelectThreads) sh.hist[b] = 0;
+template <int NT>
+__device__ __forceinline__ void hist_clear(SelectShared<NT>& sh, int nbins, int copies) {
+  for (int b = threadIdx.x; b < (copies - 1) * kHistStride + nbins; b += NT) sh.hist[b] = 0;
   __syncthreads();
 }
 
@@ -87,12 +96,13 @@ __device__ __forceinline__ void hist_clear(SelectShared& sh, int nbins, int copi
 // and reduces `remaining` to the rank inside the bin.  All threads call it.  No step waits for an LDS
 // read that depends on the previous one: the copies are summed by all threads, wave 0 finds the lane whose
 // group of bins holds the rank (suffix sums over lanes), then the bin inside that group the same way.
-__device__ __forceinline__ void hist_pick(SelectShared& sh, int nbins, int copies, int shift, uint32_t& prefix,
+template <int NT>
+__device__ __forceinline__ void hist_pick(SelectShared<NT>& sh, int nbins, int copies, int shift, uint32_t& prefix,
                                           uint32_t& remaining) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   __syncthreads();
   if (copies > 1) {                    // totals of the private copies into copy 0 (a thread touches only its own bins)
-    for (int b = threadIdx.x; b < nbins; b += kSelectThreads) {
+    for (int b = threadIdx.x; b < nbins; b += NT) {
       unsigned int c = 0;
       for (int k = 0; k < copies; ++k) c += sh.hist[k * kHistStride + b];
       sh.hist[b] = c;
@@ -134,9 +144,10 @@ __device__ __forceinline__ void hist_pick(SelectShared& sh, int nbins, int copie
 
 // Exclusive prefix counts over the workgroup for one ordered tile.  In: this thread's counts.  Out: counts
 // in lower threads of the tile, and the tile totals.  All threads call it.
-__device__ __forceinline__ void tile_scan(SelectShared& sh, int nsure, int ntie, int& before_sure, int& before_tie,
+template <int NT>
+__device__ __forceinline__ void tile_scan(SelectShared<NT>& sh, int nsure, int ntie, int& before_sure, int& before_tie,
                                           int& tot_sure, int& tot_tie) {
-  constexpr int NWV = kSelectThreads / 64;
+  constexpr int NWV = NT / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int ss = nsure, st = ntie;
 #pragma unroll
@@ -169,12 +180,13 @@ __device__ __forceinline__ void tile_scan(SelectShared& sh, int nsure, int ntie,
 //   key(j)      order-preserving integer image of its score,
 //   eligible(j) whether it competes in the radix select,
 //   forced(j)   whether it is admitted regardless (stage 2: members of the protected set).
-// The candidates are loaded once into registers, ITEMS per thread (npre <= kSelectThreads * ITEMS).
+// The candidates are loaded once into registers, ITEMS per thread (npre <= NT * ITEMS).
 // emit(j, admitted, pos) is called for every j, pos = number of admitted candidates before j.
-template <int ITEMS, class Source, class Emit>
-__device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emit, int npre, int need) {
+template <int NT, int ITEMS, class Source, class Emit>
+__device__ __forceinline__ void select_wg(SelectShared<NT>& sh, Source src, Emit emit, int npre, int need) {
   const int tid = threadIdx.x;
-  static_assert(ITEMS > 0 && ITEMS % kSelTileItems == 0 && ITEMS <= kSelMaxItems, "register-resident candidates");
+  constexpr int kSelTile = NT * kSelTileItems;
+  static_assert(ITEMS > 0 && ITEMS % kSelTileItems == 0 && ITEMS <= SelectSize<NT>::kMaxItems, "register-resident candidates");
   uint32_t keys[ITEMS];
   unsigned long long elig = 0, forc = 0;       // one bit per register slot
   // slot s of this thread holds candidate j = (s / 4) * kSelTile + tid * 4 + (s % 4): tiles in order, 4 consecutive
@@ -203,13 +215,13 @@ __device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emi
     for (int pass = 0; pass < 3; ++pass) {
       const int shift = pass_shift(pass), nbins = pass_bins(pass);
       const uint32_t himask = pass_himask(pass);
-      const int copies = pass == 0 ? kHistCopies : 1;
+      const int copies = pass == 0 ? SelectSize<NT>::kCopies : 1;
       hist_clear(sh, nbins, copies);
 #pragma unroll
       for (int s = 0; s < ITEMS; ++s) {
         const bool match = ((elig >> s) & 1ull) && (keys[s] & himask) == prefix;
-        if (pass == 0) hist_add<true>(sh, match, (keys[s] >> shift) & (uint32_t)(nbins - 1));
-        else hist_add<false>(sh, match, (keys[s] >> shift) & (uint32_t)(nbins - 1));
+        if (pass == 0) hist_add<true, NT>(sh, match, (keys[s] >> shift) & (uint32_t)(nbins - 1));
+        else hist_add<false, NT>(sh, match, (keys[s] >> shift) & (uint32_t)(nbins - 1));
       }
       hist_pick(sh, nbins, copies, shift, prefix, remaining);
     }
@@ -231,7 +243,7 @@ __device__ __forceinline__ void select_wg(SelectShared& sh, Source src, Emit emi
       const unsigned int c = fo ? 2u : (el ? (keys[s] > tau ? 2u : (keys[s] == tau ? 1u : 0u)) : 0u);
       word |= c << (8 * e);
     }
-    sh.cls_words[t * kSelectThreads + tid] = word;       // candidates 4 * (t * 1024 + tid) .. + 3
+    sh.cls_words[t * NT + tid] = word;                   // candidates 4 * (t * NT + tid) .. + 3
   }
   __syncthreads();
   unsigned int mine[T4];
@@ -296,10 +308,9 @@ struct FillSource {             // two-stage, stage 2: protected tokens are in, 
 };
 
 // additive rule: one selection on the fused scores
-template <int ITEMS>
-__global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
-  constexpr int NT = kSelectThreads;
-  __shared__ SelectShared sh;
+template <int NT, int ITEMS>
+__global__ __launch_bounds__(NT) void select_kernel(SelectArgs a) {
+  __shared__ SelectShared<NT> sh;
   const int tid = threadIdx.x;
   const int seq = blockIdx.x;
   const int lz = blockIdx.y;
@@ -320,14 +331,13 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   }
   if (npre > NT * ITEMS) return;         // the host picks ITEMS from the longest request: cannot happen
   ScoreSource src = {a.scores + (int64_t)lz * a.T + s0};
-  select_wg<ITEMS>(sh, src, [&](int j, bool admitted, int pos) { if (admitted) out[pos] = j; }, npre, need);
+  select_wg<NT, ITEMS>(sh, src, [&](int j, bool admitted, int pos) { if (admitted) out[pos] = j; }, npre, need);
 }
 
 // two-stage rule, stage 1: once per request (the prior is shared by layers and heads)
-template <int ITEMS>
-__global__ __launch_bounds__(kSelectThreads) void select_stage1_kernel(SelectArgs a) {
-  constexpr int NT = kSelectThreads;
-  __shared__ SelectShared sh;
+template <int NT, int ITEMS>
+__global__ __launch_bounds__(NT) void select_stage1_kernel(SelectArgs a) {
+  __shared__ SelectShared<NT> sh;
   __shared__ int sh_flagged;
   const int tid = threadIdx.x;
   const int seq = blockIdx.x;
@@ -359,14 +369,13 @@ __global__ __launch_bounds__(kSelectThreads) void select_stage1_kernel(SelectArg
     return;
   }
   PriorSource src = {p};
-  select_wg<ITEMS>(sh, src, [&](int j, bool admitted, int) { member[j] = admitted ? 1 : 0; }, npre, need);
+  select_wg<NT, ITEMS>(sh, src, [&](int j, bool admitted, int) { member[j] = admitted ? 1 : 0; }, npre, need);
 }
 
 // two-stage rule, stage 2: attention fills what stage 1 left
-template <int ITEMS>
-__global__ __launch_bounds__(kSelectThreads) void select_stage2_kernel(SelectArgs a) {
-  constexpr int NT = kSelectThreads;
-  __shared__ SelectShared sh;
+template <int NT, int ITEMS>
+__global__ __launch_bounds__(NT) void select_stage2_kernel(SelectArgs a) {
+  __shared__ SelectShared<NT> sh;
   const int tid = threadIdx.x;
   const int seq = blockIdx.x;
   const int lz = blockIdx.y;
@@ -387,7 +396,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_stage2_kernel(SelectArg
   }
   if (npre > NT * ITEMS) return;
   FillSource src = {a.scores + (int64_t)lz * a.T + s0, a.member + s0};
-  select_wg<ITEMS>(sh, src, [&](int j, bool admitted, int pos) { if (admitted) out[pos] = j; }, npre, need);
+  select_wg<NT, ITEMS>(sh, src, [&](int j, bool admitted, int pos) { if (admitted) out[pos] = j; }, npre, need);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -945,20 +954,32 @@ __global__ __launch_bounds__(kPartThreads) void part_emit_kernel(SelectArgs a, P
   }
 }
 
-// candidates kept in registers per thread by the one-workgroup kernels, chosen from the longest request
-static int items_for(const Plan& pl) {
+// Which one-workgroup kernel: 256 threads when every request fits 256 x 16 candidates and the batch has enough
+// problems to keep several such workgroups on every compute unit, else 1024 threads.
+static bool small_workgroups(const Plan& pl, int64_t problems) {
+  return pl.max_n - pl.W <= kSelectSmallThreads * kSelectSmallMaxItems && problems >= kSelectSmallProblems;
+}
+// candidates kept in registers per thread, chosen from the longest request
+static int items_for(const Plan& pl, int threads) {
   const int npre = pl.max_n - pl.W;
-  for (int items : {8, 16, 32, 48}) if (npre <= kSelectThreads * items) return items;
+  for (int items : {8, 16, 32, 48}) if (npre <= threads * items) return items;
   return 64;
 }
 
-#define CODECOMP_DISPATCH_ITEMS(KERNEL, GRID, ARGS)                                        \
-  switch (items_for(pl)) {                                                                 \
-    case 8: KERNEL<8><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;             \
-    case 16: KERNEL<16><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
-    case 32: KERNEL<32><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
-    case 48: KERNEL<48><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
-    default: KERNEL<64><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
+#define CODECOMP_DISPATCH_ITEMS(KERNEL, GRID, PROBLEMS, ARGS)                                              \
+  if (small_workgroups(pl, PROBLEMS)) {                                                                    \
+    switch (items_for(pl, kSelectSmallThreads)) {                                                          \
+      case 8: KERNEL<kSelectSmallThreads, 8><<<GRID, dim3(kSelectSmallThreads), 0, stream>>>(ARGS); break;   \
+      default: KERNEL<kSelectSmallThreads, 16><<<GRID, dim3(kSelectSmallThreads), 0, stream>>>(ARGS); break; \
+    }                                                                                                      \
+  } else {                                                                                                 \
+    switch (items_for(pl, kSelectThreads)) {                                                               \
+      case 8: KERNEL<kSelectThreads, 8><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;           \
+      case 16: KERNEL<kSelectThreads, 16><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;         \
+      case 32: KERNEL<kSelectThreads, 32><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;         \
+      case 48: KERNEL<kSelectThreads, 48><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;         \
+      default: KERNEL<kSelectThreads, 64><<<GRID, dim3(kSelectThreads), 0, stream>>>(ARGS); break;         \
+    }                                                                                                      \
   }
 
 static PartArgs part_args(const Plan& pl, void* workspace) {
@@ -992,7 +1013,7 @@ int launch_select(const Plan& pl, const float* scores, int32_t* idx, void* works
   a.scores = scores; a.cu_seqlens = pl.cu_seqlens_dev; a.cu_budgets = pl.cu_budgets_dev; a.idx = idx;
   a.n_seqs = pl.n_seqs; a.T = pl.T; a.TB = pl.TB; a.W = pl.W;
   if (pl.sel_parts > 0) return launch_parts<RuleAdditive>(pl, a, part_args(pl, workspace), pl.L * pl.Hkv, stream);
-  CODECOMP_DISPATCH_ITEMS(select_kernel, dim3(pl.n_seqs, pl.L * pl.Hkv), a)
+  CODECOMP_DISPATCH_ITEMS(select_kernel, dim3(pl.n_seqs, pl.L * pl.Hkv), (int64_t)pl.n_seqs * pl.L * pl.Hkv, a)
   if (hipError_t e = hipGetLastError()) return (int)e;
   return 0;
 }
@@ -1011,9 +1032,9 @@ int launch_select_two_stage(const Plan& pl, const float* scores, const float* pr
     if (int rc = launch_parts<RuleStage1>(pl, a, c, 1, stream)) return rc;
     return launch_parts<RuleStage2>(pl, a, c, pl.L * pl.Hkv, stream);
   }
-  CODECOMP_DISPATCH_ITEMS(select_stage1_kernel, dim3(pl.n_seqs), a)
+  CODECOMP_DISPATCH_ITEMS(select_stage1_kernel, dim3(pl.n_seqs), (int64_t)pl.n_seqs, a)
   if (hipError_t e = hipGetLastError()) return (int)e;
-  CODECOMP_DISPATCH_ITEMS(select_stage2_kernel, dim3(pl.n_seqs, pl.L * pl.Hkv), a)
+  CODECOMP_DISPATCH_ITEMS(select_stage2_kernel, dim3(pl.n_seqs, pl.L * pl.Hkv), (int64_t)pl.n_seqs * pl.L * pl.Hkv, a)
   if (hipError_t e = hipGetLastError()) return (int)e;
   return 0;
 }

@@ -10,7 +10,8 @@ Tensors (numpy, host):
   prior  float32             [sum N_r]                per-token structural prior, shared by
                                                       layers and heads (a property of the text)
 
-The five workload recipes follow the benchmark configurations of this repository; they stand
+The first five workload recipes follow the benchmark configurations of this repository, the sixth
+(`paper_chunks`) the compression setting of the paper's appendix; they stand
 in for repository-code contexts (head shapes of the named model families, capacity ratios in
 the paper's range, span lengths in the range of its structural spans, heavy-hitter key rows
 to mimic attention sinks).  No item of any public benchmark is used.
@@ -117,12 +118,26 @@ def ragged_agentic(n_seqs: int = 16, lo: int = 8192, hi: int = 49152) -> Workloa
     return _make("ragged_agentic", 5, 1, 28, 4, 128, lens, 64, budgets, 7, 1.0, 0.0, 0.0, (4, 12), 0.20, 0.0, 1.0)
 
 
+def paper_chunks(n_chunks: int = 64, capacity: float = 0.5) -> Workload:
+    """The compression setting of the paper's own experiments (appendix "Compression settings") on a 7B-shaped model:
+    the context comes as chunks of 128 to 4096 tokens (file-level chunks aimed at 512 tokens: lengths
+    512 * exp(0.7 z), z ~ N(0,1), clipped), every chunk is compressed on its own with a window of 128 tokens, average
+    pooling of width 5 and a capacity of 0.4 to 0.6 (here B_r = max(W, floor(capacity * N_r))); structural spans of
+    16 to 48 tokens (the paper's minimum span is 16), a quarter of them marked, binary prior."""
+    g = _rng(6, _T_LENS)
+    lens = np.clip(np.rint(512.0 * np.exp(0.7 * g.standard_normal(n_chunks))), 128, 4096).astype(np.int64)
+    budgets = [max(128, int(np.floor(capacity * n))) for n in lens]
+    return _make("paper_chunks", 6, 28, 28, 4, 128, [int(n) for n in lens], 128, budgets, 5, 1.0, 0.0, 0.0, (16, 48),
+                 0.25, 1.0, 1.0)
+
+
 CONFIGS = {
     "tiny": tiny,
     "qwen7b_32k": qwen7b_32k,
     "llama8b_64k": llama8b_64k,
     "long_128k": long_128k,
     "ragged_agentic": ragged_agentic,
+    "paper_chunks": paper_chunks,
 }
 
 

@@ -61,6 +61,14 @@ def test_ragged_agentic_full():
     run_full(w, [(0, 0, shortest), (0, 2, longest), (0, 3, 5)])
 
 
+def test_paper_chunks_full():
+    # the paper's own setting: 64 chunks of 142 .. 2313 tokens, window 128 (896 rows in two row splits), pooling 5,
+    # half of every chunk kept; the oracle scores the shortest, the longest and a middle chunk
+    w = wl.paper_chunks()
+    order = np.argsort(w.seqlens)
+    run_full(w, [(0, 0, int(order[0])), (13, 2, int(order[-1])), (27, 3, int(order[len(order) // 2])), (5, 1, 7)])
+
+
 @pytest.mark.timeout(600)
 def test_llama8b_64k_all_layers():
     # all 32 layers; the oracle scores sampled heads of the first, a middle and the last layer

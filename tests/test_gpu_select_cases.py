@@ -132,6 +132,24 @@ def test_select_by_parts_in_a_batch_of_many_requests():
     assert np.array_equal(idx.astype(np.int64), want)
 
 
+@pytest.mark.parametrize("longest", [1500, 2048, 3000, 4096, 4097])
+def test_select_with_small_workgroups(longest):
+    """Batches of requests of at most 4096 candidates with a thousand problems or more run 256-thread workgroups
+    holding 8 or 16 candidates per thread (the longest request decides; one candidate more and the 1024-thread
+    kernel runs): 120 requests x 3 rows x 3 layers, crafted rows."""
+    g = np.random.default_rng(longest)
+    lens = [int(x) + W for x in g.integers(0, min(longest, 2000), size=120)]
+    lens[0] = W; lens[7] = W + 1; lens[60] = longest + W
+    needs = [int(g.integers(0, n - W + 1)) for n in lens]
+    needs[60] = longest // 3
+    rows = np.concatenate([crafted_rows(n - W, max(1, b), seed=2000 + i)[[(i + k_) % 13 for k_ in range(3)]] if n > W
+                           else np.zeros((3, W), np.float32) for i, (n, b) in enumerate(zip(lens, needs))], axis=1)
+    idx, cu, cb = select_on_device(rows, lens, [b + W for b in needs], layers=3)
+    want = orc.select_packed(rows.astype(np.float64)[None], cu, cb, W)[0]
+    for l in range(3):
+        assert np.array_equal(idx[l].astype(np.int64), want), l
+
+
 def two_stage_on_device(rows, prior, seqlens, budgets, ratio, bmin, layers=1):
     """rows [H][T] fp32 (pooled attention), prior [T] -> idx [L][H][TB] through codecomp_select_two_stage."""
     import torch
@@ -226,6 +244,10 @@ def test_two_stage_ragged_agentic():                  # 48 per thread (longest r
 
 def test_two_stage_llama8b_64k_two_layers():          # 64 per thread, binary prior: stage 1 is all ties
     two_stage_full(wl.scaled(wl.llama8b_64k(), n_layers=2))
+
+
+def test_two_stage_paper_chunks():                    # 64 short chunks x 112 heads: 256-thread workgroups in stage 2
+    two_stage_full(wl.paper_chunks(), layers_checked=[0, 13, 27])
 
 
 def test_two_stage_long_128k_one_layer():             # selection by parts, binary prior, budget 13107
