@@ -507,6 +507,9 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     }
     soft_end(t - 1, 1, b1, fast);
     sched_phase(a1, b1, fast);
+    // pass 2 of an eight-wave workgroup: each phase a scheduling region of its own (2 % off that pass; the four-wave
+    // workgroups and pass 1 get slower with it)
+    if constexpr (PASS == 2 && NW == 8) __builtin_amdgcn_sched_barrier(0);
     if constexpr (MASKED) { mask_tail(accA0, 0); if constexpr (A1) mask_tail(accA1, 0); }
     if constexpr (FAST) {
       if (t == 0) {                             // the chunk's fixed references: largest logit this lane sees first
@@ -529,6 +532,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 3 ? 2 : 1)) void score_pass_kernel(
     }
     soft_end(t, 0, a1, fast);
     sched_phase(b1, a1, fast);
+    if constexpr (PASS == 2 && NW == 8) __builtin_amdgcn_sched_barrier(0);
     if constexpr (MASKED) { mask_tail(accB0, 1); if constexpr (B1) mask_tail(accB1, 1); }
     if constexpr (FAST && !A1 && B1) {
       if (t == 0) {                             // slot 1 sees its first logits here (a sub-tile b may hold no valid key at all)
