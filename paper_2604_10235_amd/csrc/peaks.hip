@@ -72,7 +72,10 @@ __global__ __launch_bounds__(kThreads) void valu_kernel(float* out, int iters, f
 
 // One "tile" = 64 keys for two row blocks of 32 rows: 2 phases x (8 k-steps x 2 MFMAs), and per phase the 32 logits
 // a lane holds of the previous phase go through fma, exp2, add (two per MFMA).
-__global__ __launch_bounds__(kThreads) void mix_kernel(const u32x4* __restrict__ rnd, float* out, long long* clk, int tiles, float seed) {
+// Two waves per SIMD and at most 256 registers each, like the score passes: the accumulators then stay in ordinary
+// VGPRs.  (Given 512 registers the compiler keeps them in AGPRs and copies every logit out with a v_accvgpr_read:
+// 8 instead of 6 VALU instructions per MFMA, 49 instead of 41 cycles per MFMA - a floor that no kernel has to accept.)
+__global__ __launch_bounds__(kThreads, 2) void mix_kernel(const u32x4* __restrict__ rnd, float* out, long long* clk, int tiles, float seed) {
   u32x4 a[8], b[4];
   const int lane = threadIdx.x;
 #pragma unroll
