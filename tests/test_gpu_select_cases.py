@@ -206,6 +206,26 @@ def test_random_batches_with_long_requests(seed):
         assert np.array_equal(idx2[0, :, cb[r]:cb[r + 1]].astype(np.int64), want), (seed, r, lens[r], budgets[r], ratio, bmin)
 
 
+def test_two_stage_with_small_workgroups_in_both_stages():
+    """1100 requests of at most 3000 candidates: stage 1 (one problem per request) and stage 2 both run the 256-thread
+    workgroups; priors with ties, span budgets that bind and that do not."""
+    g = np.random.default_rng(31)
+    lens = [int(x) + W for x in g.integers(0, 900, size=1100)]
+    lens[5] = W; lens[500] = 3000 + W; lens[900] = 2049 + W
+    needs = [int(g.integers(0, n - W + 1)) for n in lens]
+    total = sum(lens)
+    rows = np.round(g.standard_normal((2, total)), 1).astype(np.float32)
+    prior = np.where(g.random(total) < 0.3, np.round(g.random(total), 1) + 0.1, 0.0).astype(np.float32)
+    budgets = [b + W for b in needs]
+    for ratio, bmin in ((0.5, 0), (0.2, 40)):
+        idx, cu, cb = two_stage_on_device(rows, prior, lens, budgets, ratio, bmin)
+        for r in range(len(lens)):
+            a, e = cu[r], cu[r + 1]
+            want = orc.select_two_stage(rows[:, a:e].astype(np.float64), prior[a:e], W, budgets[r],
+                                        span_ratio=float(np.float32(ratio)), span_min=bmin)
+            assert np.array_equal(idx[0, :, cb[r]:cb[r + 1]].astype(np.int64), want), (r, lens[r], budgets[r], ratio, bmin)
+
+
 def two_stage_full(w, ratio=0.5, bmin=0, layers_checked=None):
     """Fused call in two-stage mode on a full-size workload; indices bit-equal to the oracle's two-stage rule on the
     GPU's own fp32 scores (every layer in `layers_checked`, every head, every request), gather bit-exact."""
