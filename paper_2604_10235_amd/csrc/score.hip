@@ -14,7 +14,6 @@ extern template int dispatch_waves<64, true>(const Plan&, const ScoreArgs&, hipS
 // over the (at most two) wave slots that hold a share of the row's keys.
 __global__ __launch_bounds__(256) void score_merge_kernel(ScoreArgs a) {
   __shared__ int part[256 / 64];
-  const int row = blockIdx.x * blockDim.x + threadIdx.x;
   const int seq = blockIdx.y;
   const int lz = blockIdx.z;
   // positions of the earlier requests in a problem's sequence: summed by the whole workgroup
@@ -26,13 +25,14 @@ __global__ __launch_bounds__(256) void score_merge_kernel(ScoreArgs a) {
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mine;
   __syncthreads();
   const int tile_off = a.lead + part[0] + part[1] + part[2] + part[3];
-  if (row >= a.lrows) return;
+  // a launch with many problems has one workgroup per problem (the rows in turns), else one per 256 rows
+  for (int row = blockIdx.x * blockDim.x + threadIdx.x; row < a.lrows; row += gridDim.x * blockDim.x) {
   const int split = row / (a.nb * 32);
   const int rb = (row - split * a.nb * 32) >> 5;
   const int nt = (a.cu_seqlens[seq + 1] - a.cu_seqlens[seq] - a.key_trim + kTileKeys - 1) / kTileKeys;
   if (nt == 0) {                           // no key to attend to: nothing reads this normaliser
     a.lse[((int64_t)lz * a.n_seqs + seq) * a.lrows + row] = 0.f;
-    return;
+    continue;
   }
   const int x0 = lz * a.tiles_per_problem + tile_off;
   const int g0 = wg_of_tile(x0, a.total_tiles, a.stat_teams), g1 = wg_of_tile(x0 + nt - 1, a.total_tiles, a.stat_teams);
@@ -52,6 +52,7 @@ __global__ __launch_bounds__(256) void score_merge_kernel(ScoreArgs a) {
     }
   }
   a.lse[((int64_t)lz * a.n_seqs + seq) * a.lrows + row] = M + log2f(L);
+  }
 }
 
 struct FinishArgs {
@@ -152,7 +153,8 @@ __global__ __launch_bounds__(256) void score_finish_kernel(FinishArgs a) {
 }
 
 int launch_row_merge(const Plan& pl, const ScoreArgs& a, hipStream_t stream) {
-  const dim3 mgrid((a.lrows + 255) / 256, pl.n_seqs, pl.L * pl.Hkv);
+  const bool many = (int64_t)pl.n_seqs * pl.L * pl.Hkv >= 2048;     // enough workgroups for the device as it is
+  const dim3 mgrid(many ? 1 : (a.lrows + 255) / 256, pl.n_seqs, pl.L * pl.Hkv);
   score_merge_kernel<<<mgrid, dim3(256), 0, stream>>>(a);
   if (hipError_t e = hipGetLastError()) return (int)e;
   return 0;
