@@ -97,11 +97,25 @@ __global__ __launch_bounds__(256) void score_finish_kernel(FinishArgs a) {
   const bool one_request = r_first == r_last;
   int lo_[PER], hi_[PER];               // request bounds [lo, hi) of each of this thread's tokens
   float pr[PER];
+  // A tile that meets fewer than 64 requests: every wave takes their upper bounds into one register (lane q: request
+  // r_first + q) and each token counts the bounds at or below it - one load per wave instead of a binary search per token.
+  const bool few_requests = !one_request && r_last - r_first < 64;
+  const int bound = few_requests ? a.cu_seqlens[min(r_first + 1 + (tid & 63), a.n_seqs)] : 0;
+  const int first_lo = a.cu_seqlens[r_first];
 #pragma unroll
   for (int e = 0; e < PER; ++e) {
     const int j = base + e * 256 + tid;
-    const int r = one_request || j >= a.T ? r_first : request_of(a.cu_seqlens, a.n_seqs, j);
-    lo_[e] = a.cu_seqlens[r]; hi_[e] = a.cu_seqlens[r + 1];
+    if (few_requests) {
+      int k = 0;                          // requests of the tile that end at or before token j
+      if (j < a.T)
+        for (int q = 0; q < r_last - r_first; ++q) k += j >= __builtin_amdgcn_readlane(bound, q);
+      hi_[e] = __shfl(bound, k);
+      const int below = __shfl(bound, max(k - 1, 0));       // every lane takes part: a lane reads from lanes that are not in its request
+      lo_[e] = k == 0 ? first_lo : below;
+    } else {
+      const int r = one_request || j >= a.T ? r_first : request_of(a.cu_seqlens, a.n_seqs, j);
+      lo_[e] = a.cu_seqlens[r]; hi_[e] = a.cu_seqlens[r + 1];
+    }
     pr[e] = j < a.T ? a.prior[j] : 0.f;
   }
   // the tile's own tokens: PER independent loads per thread (per row split), all in flight together
