@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcodecomp.so")
-PEAKS_LIB = os.path.join(HERE, "libcodecomp_peaks.so")      # measurement only: what the GPU sustains (peaks.hip)
+PEAKS_LIB = os.path.join(HERE, "libcodecomp_peaks.so")      # measurement only: what the GPU sustains
+PEAKS_SOURCES = ["peaks.hip", "pass_model.hip"]
 # the heavy translation units (the MFMA passes, one per head_dim and key type) first: they run side by side
 SOURCES = ["score_pass_d128_bf16.hip", "score_pass_d128_fp8.hip", "score_pass_d64_bf16.hip", "score_pass_d64_fp8.hip",
            "api.hip", "score.hip", "select.hip", "gather.hip", "structure.hip", "static_scratch.hip"]
@@ -31,8 +32,9 @@ def _compile(src: str) -> str:
 
 def build_library(verbose: bool = True) -> str:
     with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 4)) as ex:
-        objs = list(ex.map(_compile, SOURCES + ["peaks.hip"]))
-    for lib, members in ((LIB, objs[:-1]), (PEAKS_LIB, objs[-1:])):
+        objs = list(ex.map(_compile, SOURCES + PEAKS_SOURCES))
+    n = len(SOURCES)
+    for lib, members in ((LIB, objs[:n]), (PEAKS_LIB, objs[n:])):
         r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *members, "-o", lib],
                            capture_output=True, text=True)
         if r.returncode != 0:

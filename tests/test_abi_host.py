@@ -41,7 +41,7 @@ def test_peaks_library_exports_its_declared_symbol():
     text = open(os.path.join(ROOT, "include", "codecomp_peaks.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(codecomp_[a-z_]+)\s*\(", text)))
-    assert names == ["codecomp_measure_peaks"]
+    assert names == ["codecomp_measure_pass_model", "codecomp_measure_peaks"]
     lib = C.CDLL(peaks.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -53,6 +53,18 @@ def test_peaks_library_exports_its_declared_symbol():
     out = peaks.codecomp_peaks()
     assert lib.codecomp_measure_peaks(None, 0x1000, 0x1000, 1 << 20, 0x1000, C.byref(out), None) == -1
     assert lib.codecomp_measure_peaks(0x1000, 0x1000, 0x1000, 1000, 0x1000, C.byref(out), None) == -1
+    # the pass model: 12 rows of 2 int32 + 4 doubles, 4 int32 after them
+    assert C.sizeof(peaks.codecomp_pass_model_row) == 40 and C.sizeof(peaks.codecomp_pass_model) == 12 * 40 + 16
+    assert peaks.codecomp_pass_model.n_rows.offset == 480 and peaks.codecomp_pass_model.status.offset == 488
+    header = open(os.path.join(ROOT, "include", "codecomp_peaks.h")).read()
+    assert int(re.search(r"#define CODECOMP_PASS_MODEL_MAX_ROWS (\d+)", header).group(1)) == peaks.PASS_MODEL_MAX_ROWS
+    for bit, _ in peaks.PASS_MODEL_FEATURES.items():
+        assert re.search(r"#define CODECOMP_PASS_MODEL_[A-Z]+ %d\b" % bit, header), bit
+    lib.codecomp_measure_pass_model.restype = C.c_int
+    lib.codecomp_measure_pass_model.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
+    pm = peaks.codecomp_pass_model()
+    assert lib.codecomp_measure_pass_model(None, 0x1000, 1 << 30, 0x1000, C.byref(pm), None) == -1
+    assert lib.codecomp_measure_pass_model(0x1000, 0x1000, (1 << 30) + 8, 0x1000, C.byref(pm), None) == -1
 
 
 def test_selection_by_parts_shows_in_the_workspace_size():
