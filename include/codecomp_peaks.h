@@ -44,6 +44,7 @@ int codecomp_measure_peaks(const void* rnd, void* buf_a, void* buf_b, size_t byt
 #define CODECOMP_PASS_MODEL_STAGE 2     /* every thread parks 32 bytes per tile in LDS (the next tile)                  */
 #define CODECOMP_PASS_MODEL_LOADS 4     /* ... that come from global memory, 16 KB per tile and workgroup               */
 #define CODECOMP_PASS_MODEL_UNEVEN 8    /* the second wave of every SIMD carries three units per tile against four      */
+#define CODECOMP_PASS_MODEL_DIRECT 16   /* the tile's bytes go from global memory straight into LDS (no registers)      */
 #define CODECOMP_PASS_MODEL_MAX_ROWS 12
 
 typedef struct codecomp_pass_model_row {

@@ -17,19 +17,26 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 #define BC(a) __builtin_bit_cast(bf16x8, a)
 
 constexpr int kModelThreads = 512;
-constexpr int kRing = 1, kStage = 2, kLoads = 4, kUneven = 8;   // feature bits
+constexpr int kRing = 1, kStage = 2, kLoads = 4, kUneven = 8, kDirect = 16;   // feature bits
 
 // FLAGS: kRing    K fragments come from LDS through a four-entry register ring, one workgroup barrier per tile;
 //        kStage   every thread parks 32 bytes per tile in the other LDS buffer (the next tile);
 //        kLoads   those bytes come from global memory (16 KB per tile and workgroup, streamed from a region of
 //                 `big` of the workgroup's own), asked for NSETS tiles before they are parked;
 //        kUneven  waves 4..7 (the second wave of every SIMD) skip their second row block in the second half of
-//                 every tile: three (block, half-tile) units against four, as with 14 row blocks over eight waves.
+//                 every tile: three (block, half-tile) units against four, as with 14 row blocks over eight waves;
+//        kDirect  (instead of kStage | kLoads) the 16 KB of a tile go from global memory straight into LDS
+//                 (global_load_lds_dwordx4: lane i's 16 bytes land at base + 16 i, so rows cannot be padded; the
+//                 16-byte pieces of a row are XOR-swizzled with the row number instead), into a ring of four tile
+//                 buffers, NSETS tiles ahead of their use; no staging registers, no LDS stores.
 template <int FLAGS, int NSETS>
 __global__ __launch_bounds__(kModelThreads, 2) void pass_model_kernel(const u32x4* __restrict__ rnd, const u32x4* __restrict__ big,
                                                                       size_t big_n16, float* out, long long* clk, int tiles) {
   constexpr int NT = kModelThreads;
-  __shared__ u32x4 tile[2][64 * 17];               // 64 keys x 272 bytes
+  constexpr bool DIRECT = (FLAGS & kDirect) != 0;
+  constexpr int ROW = DIRECT ? 16 : 17;             // 16-byte pieces per key row in LDS (272-byte rows, or 256 swizzled)
+  constexpr int NBUF = DIRECT ? 4 : 2;
+  __shared__ u32x4 tile[NBUF][64 * ROW];
   u32x4 q[2][8], ring[4], stage[4][2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
 #pragma unroll
@@ -40,10 +47,14 @@ __global__ __launch_bounds__(kModelThreads, 2) void pass_model_kernel(const u32x
   for (int k = 0; k < 4; ++k)
 #pragma unroll
     for (int i = 0; i < 2; ++i) stage[k][i] = rnd[(i * NT + tid + 33 * k + 7) & 4095];
-  for (int i = tid; i < 2 * 64 * 17; i += NT) (&tile[0][0])[i] = rnd[i & 4095];
+  for (int i = tid; i < NBUF * 64 * ROW; i += NT) (&tile[0][0])[i] = rnd[i & 4095];
   __syncthreads();
+  // where this lane finds the fragment of k-step ks inside a 32-key half tile (in 16-byte pieces)
+  int frag_at[8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) ring[i] = tile[0][l32 * 17 + hf + i * 2];
+  for (int ks = 0; ks < 8; ++ks) frag_at[ks] = DIRECT ? l32 * 16 + ((2 * ks + hf) ^ (l32 & 7)) : l32 * 17 + hf + ks * 2;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) ring[i] = tile[0][frag_at[i]];
   f32x16 accA[2], accB[2];
 #pragma unroll
   for (int s = 0; s < 2; ++s) { accA[s] = f32x16{0}; accB[s] = f32x16{0}; }
@@ -62,7 +73,7 @@ __global__ __launch_bounds__(kModelThreads, 2) void pass_model_kernel(const u32x
   auto body = [&](auto light_t) __attribute__((always_inline)) {
     constexpr bool LIGHT = decltype(light_t)::value;
     auto one_tile = [&](int t, u32x4 (&stg)[2]) __attribute__((always_inline)) {
-      const int buf = t & 1;
+      const int buf = DIRECT ? (t & 3) : (t & 1);
       auto phase = [&](auto ph_t) __attribute__((always_inline)) {
         constexpr int ph = decltype(ph_t)::value;
         f32x16* nn = ph == 0 ? accA : accB;
@@ -71,7 +82,20 @@ __global__ __launch_bounds__(kModelThreads, 2) void pass_model_kernel(const u32x
         constexpr bool s1_old = !(LIGHT && ph == 0);      // ... has logits of the previous half tile to consume
         constexpr int PER = s1_old ? 2 : 1;               // logits per gap (one gap after every MFMA position)
         float sum0 = 0.f, sum1 = 0.f;
-        if (ph == 0) {
+        if (ph == 0 && DIRECT) {
+          // tile t + NSETS: this thread's two pieces, the global piece chosen so that it lands swizzled
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            const int chunk = wave * 2 + i;                          // 4 key rows = 64 pieces = one instruction of a wave
+            const int r = 4 * chunk + (lane >> 4);
+            const u32x4* from = src + pos + r * 16 + ((lane & 15) ^ (r & 7));
+            const unsigned to = (unsigned)(size_t)(&tile[(t + NSETS) & 3][chunk * 64]);   // LDS byte address, the same in every lane
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(to)), "v"(from) : "memory", "m0");
+          }
+          pos += 2 * NT;
+          if (pos + 2 * NT > per_wg) pos = 0;
+        }
+        if (ph == 0 && !DIRECT) {
           if (FLAGS & kStage) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) { const int cidx = tid + i * NT; tile[buf ^ 1][(cidx >> 4) * 17 + (cidx & 15)] = stg[i]; }
@@ -97,12 +121,18 @@ __global__ __launch_bounds__(kModelThreads, 2) void pass_model_kernel(const u32x
         };
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-          if ((FLAGS & kRing) && ph == 1 && ks == 4) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+          if ((FLAGS & kRing) && ph == 1 && ks == 4) {
+            // tile t + 1 must be whole: its two loads of this thread are the oldest of 2 * NSETS in flight
+            if (DIRECT) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * (NSETS - 1)) : "memory");
+            else asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+          }
           nn[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(BC(q[0][ks]), BC(ring[ks & 3]), ks == 0 ? zero : nn[0], 0, 0, 0);
           soft(2 * ks);
           if (s1_new) nn[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(BC(q[1][ks]), BC(ring[ks & 3]), ks == 0 ? zero : nn[1], 0, 0, 0);
-          if (FLAGS & kRing)
-            ring[ks & 3] = tile[(ks + 4 < 8) ? buf : (ph == 0 ? buf : buf ^ 1)][((ph ^ (ks + 4 >= 8)) * 32 + l32) * 17 + hf + ((ks + 4) & 7) * 2];
+          if (FLAGS & kRing) {
+            const int from_buf = (ks + 4 < 8 || ph == 0) ? buf : (DIRECT ? (buf + 1) & 3 : buf ^ 1);
+            ring[ks & 3] = tile[from_buf][(ph ^ (ks + 4 >= 8)) * 32 * ROW + frag_at[(ks + 4) & 7]];
+          }
           soft(2 * ks + 1);
         }
 #pragma unroll
@@ -124,6 +154,7 @@ __global__ __launch_bounds__(kModelThreads, 2) void pass_model_kernel(const u32x
     else { for (int t = 0; t < tiles; t += 4) { one_tile(t, stage[0]); one_tile(t + 1, stage[1]); one_tile(t + 2, stage[2]); one_tile(t + 3, stage[3]); } }
   };
   if ((FLAGS & kUneven) && wave >= 4) body(std::true_type{}); else body(std::false_type{});
+  if (DIRECT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // no load into LDS is left in flight when the wave ends
   const long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
   float s = tot;
 #pragma unroll
@@ -155,11 +186,11 @@ int run_variant(const u32x4* rnd, const u32x4* big, size_t big_n16, float* sink,
   const double mfmas_per_simd = (double)tiles * 8.0 * units * 2.0;        // two waves per SIMD
   const double clock_hz = cyc[1] > 0 ? (double)cyc[0] / ((double)cyc[1] * 1e-8) : 0.0;
   row->features = FLAGS;
-  row->tiles_ahead = (FLAGS & kLoads) ? NSETS : 0;
+  row->tiles_ahead = (FLAGS & (kLoads | kDirect)) ? NSETS : 0;
   row->logits_per_s = mfmas_per_simd * 4.0 * cus * 128.0 / (ms * 1e-3);
   row->clock_mhz = clock_hz / 1e6;
   row->cycles_per_mfma = ms * 1e-3 * clock_hz / mfmas_per_simd;
-  row->hbm_gbs = (FLAGS & kLoads) ? (double)g * tiles * 16384.0 / (ms * 1e-3) / 1e9 : 0.0;
+  row->hbm_gbs = (FLAGS & (kLoads | kDirect)) ? (double)g * tiles * 16384.0 / (ms * 1e-3) / 1e9 : 0.0;
   return 0;
 }
 
@@ -191,6 +222,9 @@ extern "C" int codecomp_measure_pass_model(const void* rnd, const void* big, siz
   if ((rc = run_variant<kRing | kStage | kLoads | kUneven, 2>(r, b, n16, sink, clk, cus, s, e0, e1, &out->rows[i++]))) goto done;
   if ((rc = run_variant<kRing | kStage | kLoads | kUneven, 4>(r, b, n16, sink, clk, cus, s, e0, e1, &out->rows[i++]))) goto done;
   if ((rc = run_variant<kRing | kLoads, 2>(r, b, n16, sink, clk, cus, s, e0, e1, &out->rows[i++]))) goto done;
+  if ((rc = run_variant<kRing | kDirect, 2>(r, b, n16, sink, clk, cus, s, e0, e1, &out->rows[i++]))) goto done;
+  if ((rc = run_variant<kRing | kDirect, 3>(r, b, n16, sink, clk, cus, s, e0, e1, &out->rows[i++]))) goto done;
+  if ((rc = run_variant<kRing | kDirect | kUneven, 3>(r, b, n16, sink, clk, cus, s, e0, e1, &out->rows[i++]))) goto done;
 done:
   out->n_rows = i;
   (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);

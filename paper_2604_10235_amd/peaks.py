@@ -30,7 +30,8 @@ class codecomp_pass_model_row(C.Structure):
 
 
 PASS_MODEL_MAX_ROWS = 12
-PASS_MODEL_FEATURES = {1: "LDS ring + barrier", 2: "staging writes", 4: "global loads", 8: "uneven waves"}
+PASS_MODEL_FEATURES = {1: "LDS ring + barrier", 2: "staging writes", 4: "global loads", 16: "loads straight into LDS",
+                       8: "uneven waves"}
 
 
 class codecomp_pass_model(C.Structure):
