@@ -35,8 +35,9 @@ __global__ __launch_bounds__(kModelThreads, 2) void pass_model_kernel(const u32x
   constexpr int NT = kModelThreads;
   constexpr bool DIRECT = (FLAGS & kDirect) != 0;
   constexpr int ROW = DIRECT ? 16 : 17;             // 16-byte pieces per key row in LDS (272-byte rows, or 256 swizzled)
-  constexpr int NBUF = DIRECT ? 4 : 2;
-  __shared__ u32x4 tile[NBUF][64 * ROW];
+  constexpr int NBUF = DIRECT ? (NSETS > 3 ? 8 : 4) : 2;      // LDS tile buffers (128 KB with eight: dynamic shared memory)
+  extern __shared__ u32x4 tile_mem[];
+  u32x4 (*tile)[64 * ROW] = reinterpret_cast<u32x4 (*)[64 * ROW]>(tile_mem);
   u32x4 q[2][8], ring[4], stage[4][2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
 #pragma unroll
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(kModelThreads, 2) void pass_model_kernel(const u32x
   auto body = [&](auto light_t) __attribute__((always_inline)) {
     constexpr bool LIGHT = decltype(light_t)::value;
     auto one_tile = [&](int t, u32x4 (&stg)[2]) __attribute__((always_inline)) {
-      const int buf = DIRECT ? (t & 3) : (t & 1);
+      const int buf = t & (NBUF - 1);
       auto phase = [&](auto ph_t) __attribute__((always_inline)) {
         constexpr int ph = decltype(ph_t)::value;
         f32x16* nn = ph == 0 ? accA : accB;
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(kModelThreads, 2) void pass_model_kernel(const u32x
             const int chunk = wave * 2 + i;                          // 4 key rows = 64 pieces = one instruction of a wave
             const int r = 4 * chunk + (lane >> 4);
             const u32x4* from = src + pos + r * 16 + ((lane & 15) ^ (r & 7));
-            const unsigned to = (unsigned)(size_t)(&tile[(t + NSETS) & 3][chunk * 64]);   // LDS byte address, the same in every lane
+            const unsigned to = (unsigned)(size_t)(&tile[(t + NSETS) & (NBUF - 1)][chunk * 64]);   // LDS byte address, the same in every lane
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(to)), "v"(from) : "memory", "m0");
           }
           pos += 2 * NT;
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(kModelThreads, 2) void pass_model_kernel(const u32x
           soft(2 * ks);
           if (s1_new) nn[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(BC(q[1][ks]), BC(ring[ks & 3]), ks == 0 ? zero : nn[1], 0, 0, 0);
           if (FLAGS & kRing) {
-            const int from_buf = (ks + 4 < 8 || ph == 0) ? buf : (DIRECT ? (buf + 1) & 3 : buf ^ 1);
+            const int from_buf = (ks + 4 < 8 || ph == 0) ? buf : (buf + 1) & (NBUF - 1);
             ring[ks & 3] = tile[from_buf][(ph ^ (ks + 4 >= 8)) * 32 * ROW + frag_at[(ks + 4) & 7]];
           }
           soft(2 * ks + 1);
@@ -151,7 +152,7 @@ __global__ __launch_bounds__(kModelThreads, 2) void pass_model_kernel(const u32x
     // register set t % NSETS holds tile t + 1 and is refilled for tile t + 1 + NSETS (tiles is a multiple of 12)
     if constexpr (NSETS == 2) { for (int t = 0; t < tiles; t += 2) { one_tile(t, stage[0]); one_tile(t + 1, stage[1]); } }
     else if constexpr (NSETS == 3) { for (int t = 0; t < tiles; t += 3) { one_tile(t, stage[0]); one_tile(t + 1, stage[1]); one_tile(t + 2, stage[2]); } }
-    else { for (int t = 0; t < tiles; t += 4) { one_tile(t, stage[0]); one_tile(t + 1, stage[1]); one_tile(t + 2, stage[2]); one_tile(t + 3, stage[3]); } }
+    else { for (int t = 0; t < tiles; t += 4) { one_tile(t, stage[0]); one_tile(t + 1, stage[1]); one_tile(t + 2, stage[2]); one_tile(t + 3, stage[3]); } }   // also the direct variants further ahead (no register sets)
   };
   if ((FLAGS & kUneven) && wave >= 4) body(std::true_type{}); else body(std::false_type{});
   if (DIRECT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // no load into LDS is left in flight when the wave ends
@@ -171,12 +172,16 @@ int run_variant(const u32x4* rnd, const u32x4* big, size_t big_n16, float* sink,
   constexpr int tiles = 3000;                       // a multiple of 12; ~5 ms
   int occ = 0;
   hipError_t e;
-  if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, pass_model_kernel<FLAGS, NSETS>, kModelThreads, 0))) return (int)e;
+  constexpr bool DIRECT = (FLAGS & kDirect) != 0;
+  constexpr size_t lds = (size_t)(DIRECT ? (NSETS > 3 ? 8 : 4) : 2) * 64 * (DIRECT ? 16 : 17) * sizeof(u32x4);   // as in the kernel
+  if (lds > 65536 && (e = hipFuncSetAttribute(reinterpret_cast<const void*>(pass_model_kernel<FLAGS, NSETS>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds))) return (int)e;
+  if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, pass_model_kernel<FLAGS, NSETS>, kModelThreads, lds))) return (int)e;
   if (occ < 1) return -2;
   const int g = cus;                                // one workgroup per compute unit, as the eight-wave passes
-  pass_model_kernel<FLAGS, NSETS><<<g, kModelThreads, 0, s>>>(rnd, big, big_n16, sink, clk, tiles);   // warm-up
+  pass_model_kernel<FLAGS, NSETS><<<g, kModelThreads, lds, s>>>(rnd, big, big_n16, sink, clk, tiles);   // warm-up
   if ((e = hipEventRecord(e0, s))) return (int)e;
-  pass_model_kernel<FLAGS, NSETS><<<g, kModelThreads, 0, s>>>(rnd, big, big_n16, sink, clk, tiles);
+  pass_model_kernel<FLAGS, NSETS><<<g, kModelThreads, lds, s>>>(rnd, big, big_n16, sink, clk, tiles);
   if ((e = hipEventRecord(e1, s)) || (e = hipEventSynchronize(e1)) || (e = hipGetLastError())) return (int)e;
   float ms = 0.f;
   if ((e = hipEventElapsedTime(&ms, e0, e1))) return (int)e;
@@ -224,7 +229,8 @@ extern "C" int codecomp_measure_pass_model(const void* rnd, const void* big, siz
   if ((rc = run_variant<kRing | kLoads, 2>(r, b, n16, sink, clk, cus, s, e0, e1, &out->rows[i++]))) goto done;
   if ((rc = run_variant<kRing | kDirect, 2>(r, b, n16, sink, clk, cus, s, e0, e1, &out->rows[i++]))) goto done;
   if ((rc = run_variant<kRing | kDirect, 3>(r, b, n16, sink, clk, cus, s, e0, e1, &out->rows[i++]))) goto done;
-  if ((rc = run_variant<kRing | kDirect | kUneven, 3>(r, b, n16, sink, clk, cus, s, e0, e1, &out->rows[i++]))) goto done;
+  if ((rc = run_variant<kRing | kDirect, 6>(r, b, n16, sink, clk, cus, s, e0, e1, &out->rows[i++]))) goto done;
+  if ((rc = run_variant<kRing | kDirect | kUneven, 6>(r, b, n16, sink, clk, cus, s, e0, e1, &out->rows[i++]))) goto done;
 done:
   out->n_rows = i;
   (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
