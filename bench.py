@@ -133,6 +133,9 @@ def main() -> int:
     ap.add_argument("--layer-slices", type=int, default=1,
                     help="experiment on K's second read: run the whole path slice by slice over this many slices of "
                          "consecutive layers (1 = all layers in one call, the product's way); only the fused loop is timed")
+    ap.add_argument("--operands", default="workload", choices=["workload", "zero_keys", "one_key", "zero_queries"],
+                    help="experiment on the power limit: the same launches with keys that are all zero, all equal to "
+                         "key 0, or with all-zero queries (results are checked like any other, the figures belong to no workload)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of 1 GiB (reads 1 GiB, writes 1 GiB): the reference "
                          "dispatch for scaling FETCH_SIZE / WRITE_SIZE counter readings")
@@ -164,6 +167,14 @@ def main() -> int:
     q, k, v, prior = wl.make_all(w, threads=min(16, os.cpu_count() or 8))
     if args.kv_dtype == "fp8_e4m3":
         k, v = wl.bf16_bits_to_fp8_codes(k), wl.bf16_bits_to_fp8_codes(v)
+    if args.operands == "zero_keys":
+        k = np.zeros_like(k)
+    elif args.operands == "one_key":
+        k = np.ascontiguousarray(np.broadcast_to(k[:, :, :1, :], k.shape))
+    elif args.operands == "zero_queries":
+        q = np.zeros_like(q)
+    if args.operands != "workload":
+        w = wl.scaled(w, name=f"{w.name} with operands {args.operands}")
     t_gen = time.time() - t0
     prob = binding.DeviceProblem(w, q, k, v, prior)
     torch.cuda.synchronize()
