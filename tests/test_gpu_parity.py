@@ -353,6 +353,17 @@ def test_many_short_requests():
     run_case(w)
 
 
+def test_very_many_very_short_requests():
+    """400 packed requests of 8..24 tokens with a window of 4: a 2048-token tile of the pooling kernel meets over a
+    hundred requests (beyond the 64 whose bounds a wave keeps in one register, so every token looks its request up),
+    and most requests are shorter than two pooling widths."""
+    rng = np.random.default_rng(8)
+    lens = [int(x) for x in rng.integers(8, 25, size=400)]
+    w = wl.scaled(wl.ragged_agentic(), seqlens=lens, budgets=[max(4, n // 2) for n in lens], window=4,
+                  n_kv_heads=2, n_q_heads=4)
+    run_case(w)
+
+
 def test_compress_replays_from_a_hip_graph():
     """The fused call captured into a graph: no allocation, no synchronisation, no memset inside.  Replays are
     interleaved with eager work on other inputs and must reproduce the eager result bit for bit every time."""
