@@ -67,6 +67,47 @@ def test_peaks_library_exports_its_declared_symbol():
     assert lib.codecomp_measure_pass_model(0x1000, 0x1000, (1 << 30) + 8, 0x1000, C.byref(pm), None) == -1
 
 
+def test_headers_compile_as_plain_c_and_a_c_program_links(tmp_path):
+    """The boundary is a C ABI: both headers go through a C99 compiler with warnings as errors, and a C program that
+    calls the host-only entry points links against the library and gets the binding's answers."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "abi.c"
+    src.write_text(r"""
+#include <stdio.h>
+#include <string.h>
+#include "codecomp.h"
+#include "codecomp_peaks.h"
+int main(void) {
+  codecomp_params p;
+  int32_t cu[2] = {0, 4096}, cb[2] = {0, 512};
+  memset(&p, 0, sizeof p);
+  p.n_layers = 2; p.n_q_heads = 8; p.n_kv_heads = 2; p.head_dim = 128; p.window = 64; p.pool_kernel = 7;
+  p.prior_weight = 1.0f; p.n_seqs = 1;
+  p.cu_seqlens_host = cu; p.cu_budgets_host = cb;
+  p.cu_seqlens_dev = (const int32_t*)(size_t)4096; p.cu_budgets_dev = (const int32_t*)(size_t)4096;   /* never read here */
+  printf("%d %zu %zu %d %s\n", codecomp_validate(&p), codecomp_workspace_bytes(&p), sizeof p, codecomp_version(),
+         codecomp_status_string(CODECOMP_EINVAL_POOL));
+  p.pool_kernel = 4;
+  printf("%d\n", codecomp_validate(&p));
+  return 0;
+}
+""")
+    exe = tmp_path / "abi"
+    libdir = os.path.dirname(b.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-l:libcodecomp.so", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    rc, ws, size, version, text = out[0].split(" ", 4)
+    p = good(n_layers=2, n_q_heads=8, n_kv_heads=2, head_dim=128, window=64, pool_kernel=7,
+             cu_seqlens_host=np.array([0, 4096]), cu_budgets_host=np.array([0, 512]))
+    assert int(rc) == 0 and int(ws) == b.codecomp_workspace_bytes(p) and int(size) == C.sizeof(b.codecomp_params)
+    assert int(version) == b.version() and text == b.status_string(-5)
+    assert int(out[1]) == -5
+
+
 def test_selection_by_parts_shows_in_the_workspace_size():
     # a request beyond 65536 candidates (or a long one among few problems) is selected by parts of 8192 candidates:
     # 2048 16-bit counts per (layer * head, part)
