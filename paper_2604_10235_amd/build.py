@@ -12,6 +12,8 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcodecomp.so")
 PEAKS_LIB = os.path.join(HERE, "libcodecomp_peaks.so")      # measurement only: what the GPU sustains
 PEAKS_SOURCES = ["peaks.hip", "pass_model.hip"]
+ABI_DEMO = os.path.join(HERE, "abi_demo.exe")                # csrc/abi_demo.c: the C ABI used from plain C
+ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 # the heavy translation units (the MFMA passes, one per head_dim and key type) first: they run side by side
 SOURCES = ["score_pass_d128_bf16.hip", "score_pass_d128_fp8.hip", "score_pass_d64_bf16.hip", "score_pass_d64_fp8.hip",
            "api.hip", "score.hip", "select.hip", "gather.hip", "structure.hip", "static_scratch.hip"]
@@ -40,6 +42,14 @@ def build_library(verbose: bool = True) -> str:
         if r.returncode != 0:
             sys.stderr.write(r.stdout + r.stderr)
             raise RuntimeError("link failed")
+    # a C99 program that uses the library through its C ABI alone (tests/test_gpu_parity.py runs it on the GPU)
+    r = subprocess.run(["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROCM, "include"),
+                        "-I", os.path.join(os.path.dirname(HERE), "include"), os.path.join(CSRC, "abi_demo.c"), "-o", ABI_DEMO,
+                        "-L", HERE, "-l:libcodecomp.so", "-L", os.path.join(ROCM, "lib"), "-lamdhip64",
+                        "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(ROCM, "lib")], capture_output=True, text=True)
+    if r.returncode != 0:
+        sys.stderr.write(r.stdout + r.stderr)
+        raise RuntimeError("building abi_demo failed")
     if verbose:
         print("built", LIB)
     return LIB

@@ -523,3 +523,14 @@ def test_readme_example_runs_as_written():
     assert all(np.isin(marked, idx[l, h]).all() for l in range(idx.shape[0]) for h in range(idx.shape[1]))
     want = torch.gather(k, 2, ns["idx"].long().unsqueeze(-1).expand(-1, -1, -1, k.shape[-1]))
     assert torch.equal(k_out, want)
+
+
+def test_a_plain_c_program_compresses_through_the_c_abi():
+    """csrc/abi_demo.c (built with the library): HIP runtime + codecomp.h only, no Python in the call path; it checks
+    its own outputs and says so."""
+    import os
+    import subprocess
+    from paper_2604_10235_amd import build
+    assert os.path.exists(build.ABI_DEMO), "abi_demo.exe is missing: build first (python -m paper_2604_10235_amd.build)"
+    r = subprocess.run([build.ABI_DEMO], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.startswith("abi_demo: ok"), (r.returncode, r.stdout, r.stderr)
