@@ -510,9 +510,9 @@ def test_readme_example_runs_as_written():
     import os
     import torch
     text = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "README.md")).read()
-    start = text.index("    import numpy as np, torch")
-    end = text.index("Out of scope:")
-    code = "\n".join(line[4:] for line in text[start:end].splitlines())
+    lines = text[text.index("    import numpy as np, torch"):].splitlines()
+    stop = next(i for i, line in enumerate(lines) if line.strip() and not line.startswith("    "))   # end of the indented block
+    code = "\n".join(line[4:] for line in lines[:stop])
     ns = {}
     exec(compile(code, "README.md", "exec"), ns)
     torch.cuda.synchronize()
